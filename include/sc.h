@@ -1,0 +1,182 @@
+/*
+ * sc.h — C ABI of the MI355X (gfx950) sparse 3-D convolution path.
+ *
+ * The three steps are the ones the paper gives for every sparse-convolution operator
+ * (Section III-C: "create location table, create offset table, compute result"):
+ *
+ *     sc_hash_build   location table: coordinate -> input row        (Section III-C.1)
+ *     sc_kmap_build   offset table / rulebook of (in,out) pairs       (Section III-C.2, III-B, III-D)
+ *     sc_conv_fwd     out[o] = sum_k sum_{(i,o) in M_k} in[i] . W[k]   (Algorithm 2, Section III-C.3)
+ *
+ * Data model (Section II-A, Fig. 2; Section III-A): a sparse tensor is an index array of
+ * int32 rows (batch, x, y, z), rows distinct, plus a feature array with one row of C channels
+ * per index row.  Plain arrays in, plain arrays out; no framework types cross this boundary.
+ *
+ * Conventions
+ *   - Every pointer named d_* is DEVICE memory owned by the caller, 16-byte aligned, and only
+ *     borrowed for the duration of the stream work the call enqueues.  Pointers named h_* are
+ *     host memory.  The library allocates nothing on the device and keeps no global state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls except
+ *     sc_counts_read and sc_kmap_export_host-style readers are asynchronous on that stream and
+ *     never synchronise.
+ *   - Every function returns an int status: SC_OK or a negative SC_E* code.  Argument errors
+ *     are detected on the host before anything is enqueued.  Data-dependent errors (duplicate
+ *     or out-of-domain coordinates, table overflow) are latched by the kernels into
+ *     sc_counts.status on the device and reported by sc_counts_read.
+ *   - Coordinate domain: 0 <= b, x, y, z <= SC_COORD_MAX (16 bits each; the all-ones key is
+ *     reserved as the empty marker).  1 <= n <= SC_N_MAX rows (n = 0 is accepted and yields
+ *     empty results).  Neighbour probes that leave the domain simply miss; nothing wraps.
+ *   - Kernel offsets d in {0..K-1}^3 are numbered k = dX*K^2 + dY*K + dZ (Section III-B eq. 5).
+ *     A pair (in = i, out = o) belongs to offset k iff p_i = q_o*stride + d_k - pad, batch
+ *     equal, with pad = (K-1)/2 for submanifold layers and 0 for strided ones (the direction
+ *     is the one the offset-table figure of Section III-C shows: column 8 of a 3x3 row holds
+ *     the (+1,+1) neighbour).
+ *   - Weights are [K^3][C_in][C_out], row-major (one C_in x C_out matrix per offset).
+ *     Algorithm 2 indexes them [C_out][K^3][C_in]; that is a relabelling of the same numbers.
+ */
+#ifndef SC_H_
+#define SC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define SC_OK        0
+#define SC_EINVAL   (-1)   /* bad argument: null / misaligned pointer, unsupported K, stride, mode, dtype, channels */
+#define SC_ERANGE   (-2)   /* a coordinate lies outside the key domain */
+#define SC_EDUP     (-3)   /* the same coordinate appears twice in the input */
+#define SC_ECAP     (-4)   /* a caller-provided buffer is too small */
+#define SC_EHIP     (-5)   /* the HIP runtime reported an error */
+#define SC_EFULL    (-6)   /* hash table overflow (cannot happen with a table sized by sc_hash_bytes) */
+
+/* layer kinds */
+#define SC_SUBM      0     /* submanifold: outputs = inputs, stride 1, K odd (Section II-B) */
+#define SC_STRIDED   1     /* "normal" down-sampling sparse convolution (Section III-B, III-D) */
+
+/* element types of features and weights */
+#define SC_F32       0
+#define SC_F16       1
+#define SC_BF16      2
+
+#define SC_COORD_MAX 65534
+#define SC_N_MAX     67108864LL   /* 2^26 rows: kernel-map entries pack (row, 6-bit slot) in 32 bits */
+#define SC_K_MAX     7            /* K^3 <= 343 */
+
+/* Data-dependent results, kept on the device until the caller asks for them. */
+typedef struct sc_counts {
+    int64_t n_in;              /* rows given to sc_hash_build / sc_kmap_build */
+    int64_t n_out;             /* output rows of the last sc_kmap_build */
+    int64_t n_pairs;           /* P: (in,out) pairs over all offsets (filled by sc_counts_read) */
+    int32_t per_offset[343];   /* pairs per offset k (filled by sc_counts_read) */
+    int32_t status;            /* 0, or the first SC_E* a kernel latched */
+} sc_counts;
+
+/* ---- location table (Section III-C.1; the paper offers a dense array or a hash table, this
+ * library uses an open-addressing hash table keyed on the packed 64-bit (b,x,y,z)) ---------- */
+
+/* Bytes of the table for n keys (capacity = power of two >= 2n, so the load factor is <= 1/2). */
+size_t sc_hash_bytes(int64_t n);
+
+/* Build the table coordinate -> row index over d_coords [n][4] (b,x,y,z).  Also resets
+ * *d_counts (n_in = n, everything else 0).  Latches SC_ERANGE / SC_EDUP into d_counts->status.
+ * d_table: table_bytes >= sc_hash_bytes(n) bytes, fully overwritten. */
+int sc_hash_build(const int32_t* d_coords, int64_t n,
+                  void* d_table, size_t table_bytes,
+                  sc_counts* d_counts, void* stream);
+
+/* ---- offset table / kernel map (Section III-C.2 for submanifold layers: probe the K^3
+ * neighbours of every active site in the location table; Section III-B eq. 1-5 and
+ * Section III-D for strided layers: cell index floor(p/s), in-cell offset, distinct output
+ * cells counted and numbered) ------------------------------------------------------------- */
+
+/* Upper bound on output rows for n inputs: n for SC_SUBM and for SC_STRIDED with K == stride. */
+int64_t sc_out_bound(int64_t n, int K, int stride, int mode);
+
+/* Bytes of the kernel-map blob and of the scratch buffer sc_kmap_build needs (0 = unsupported). */
+size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode);
+size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode);
+
+/* Build the kernel map.
+ *   d_table       table built by sc_hash_build over the same d_coords (required for SC_SUBM;
+ *                 ignored for SC_STRIDED with K == stride, may be NULL there)
+ *   mode          SC_SUBM (stride must be 1, K odd, K <= SC_K_MAX) or SC_STRIDED (K == stride,
+ *                 2 <= K <= 4; other K/stride combinations return SC_EINVAL)
+ *   d_out_coords  [sc_out_bound][4]; receives the output coordinates.  SC_SUBM: may be NULL
+ *                 (outputs are the inputs, same order).  SC_STRIDED: required; output o is the
+ *                 o-th distinct cell in order of first occurrence in the input, so the result
+ *                 does not depend on thread timing.
+ *   d_kmap        opaque blob, kmap_bytes >= sc_kmap_bytes(...).  Layout (tile-major): outputs
+ *                 are cut into tiles of 64 consecutive rows; each tile holds its pairs grouped
+ *                 by offset k, ordered by output row inside one offset.  Read it with
+ *                 sc_kmap_export; feed it to sc_conv_fwd.
+ *   d_scratch     scratch_bytes >= sc_kmap_scratch_bytes(...); contents undefined afterwards.
+ *   d_counts      n_out is written here (device side); errors are latched into status. */
+int sc_kmap_build(const int32_t* d_coords, int64_t n,
+                  const void* d_table,
+                  int K, int stride, int mode,
+                  int32_t* d_out_coords,
+                  void* d_kmap, size_t kmap_bytes,
+                  void* d_scratch, size_t scratch_bytes,
+                  sc_counts* d_counts, void* stream);
+
+/* ---- compute (Algorithm 2; Section III-C.3) ---------------------------------------------- */
+
+/* Workspace sc_conv_fwd needs for the given layer (re-laid-out weights); may be 0. */
+size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_in);
+
+/* d_feat_out[o][:] = sum over offsets k and pairs (i,o) of d_feat_in[i][:] . d_weight[k]
+ *   d_feat_in   [n_in][C_in]  of dtype_in
+ *   d_weight    [K^3][C_in][C_out] of dtype_in
+ *   d_feat_out  [n_out_cap][C_out] of dtype_out; rows [0, n_out) are fully overwritten (a row
+ *               with no pair becomes 0), rows >= n_out are left untouched.  n_out is read on
+ *               the device from d_counts; n_out_cap >= sc_out_bound(...) is always enough.
+ *   d_kmap      blob from sc_kmap_build for the same (n_in, K, stride, mode)
+ *   dtype_in    SC_F32 (plain fp32 FMA) or SC_F16 / SC_BF16 (MFMA, fp32 accumulation)
+ *   dtype_out   SC_F32 or the same as dtype_in (one round-to-nearest-even at the end)
+ *   channels    SC_F32: any C_in, C_out >= 1.  SC_F16 / SC_BF16: C_in a multiple of 32 and
+ *               C_out a multiple of 16, both <= 256.
+ *   d_workspace workspace_bytes >= sc_conv_workspace_bytes(...); contents undefined afterwards */
+int sc_conv_fwd(const void* d_feat_in, int64_t n_in,
+                const void* d_weight,
+                void* d_feat_out, int64_t n_out_cap,
+                const void* d_kmap, size_t kmap_bytes,
+                const sc_counts* d_counts,
+                int K, int stride, int mode,
+                int C_in, int C_out, int dtype_in, int dtype_out,
+                void* d_workspace, size_t workspace_bytes,
+                void* stream);
+
+/* ---- reading results back ------------------------------------------------------------------ */
+
+/* Fill n_pairs and per_offset from the kernel map (d_kmap may be NULL to skip that), copy the
+ * block to h_counts and SYNCHRONISE the stream.  Returns h_counts->status if it is an error,
+ * else SC_OK.  (n, K, stride, mode) must be the ones the map was built with. */
+int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts,
+                   const void* d_kmap, int64_t n, int K, int stride, int mode,
+                   void* stream);
+
+/* Rulebook in its plain form, for inspection and tests: pairs grouped by offset,
+ * d_pairs_in / d_pairs_out [n_pairs] and d_offset_start [K^3+1] (int32, device memory; pairs of
+ * offset k are [offset_start[k], offset_start[k+1])).  The order of pairs inside one offset is
+ * unspecified.  h_counts must come from sc_counts_read on the same map (it gives the sizes).
+ * Asynchronous on `stream`. */
+int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, int mode,
+                   const sc_counts* h_counts,
+                   int32_t* d_pairs_in, int32_t* d_pairs_out, int32_t* d_offset_start,
+                   void* stream);
+
+/* Look up coordinates in a table built by sc_hash_build: d_rows[i] = row index of d_query[i],
+ * or -1 if absent.  (Not on the layer's hot path; lets callers and tests read the table.) */
+int sc_hash_lookup(const void* d_table, int64_t n_table,
+                   const int32_t* d_query, int64_t n_query, int32_t* d_rows, void* stream);
+
+const char* sc_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SC_H_ */

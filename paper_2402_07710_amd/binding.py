@@ -1,0 +1,227 @@
+"""ctypes binding of libsc.so: the same calls as include/sc.h, taking torch tensors.
+
+Argument marshalling only - every step of the path runs in the library's HIP kernels.  PyTorch
+supplies device memory (tensors) and the stream.  There is no CPU fallback: if the library has
+not been built, or no GPU is present when a call needs one, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsc.so")
+
+SC_OK, SC_EINVAL, SC_ERANGE, SC_EDUP, SC_ECAP, SC_EHIP, SC_EFULL = 0, -1, -2, -3, -4, -5, -6
+SC_SUBM, SC_STRIDED = 0, 1
+SC_F32, SC_F16, SC_BF16 = 0, 1, 2
+SC_COORD_MAX, SC_N_MAX, SC_K_MAX = 65534, 1 << 26, 7
+MODES = {"subm": SC_SUBM, "strided": SC_STRIDED, SC_SUBM: SC_SUBM, SC_STRIDED: SC_STRIDED}
+DTYPES = {"f32": SC_F32, "f16": SC_F16, "bf16": SC_BF16,
+          torch.float32: SC_F32, torch.float16: SC_F16, torch.bfloat16: SC_BF16}
+TORCH_DTYPES = {SC_F32: torch.float32, SC_F16: torch.float16, SC_BF16: torch.bfloat16}
+
+# every symbol include/sc.h declares
+SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
+           "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_conv_workspace_bytes", "sc_conv_fwd",
+           "sc_counts_read", "sc_kmap_export", "sc_strerror"]
+
+
+class ScCounts(ctypes.Structure):
+    _fields_ = [("n_in", ctypes.c_int64), ("n_out", ctypes.c_int64), ("n_pairs", ctypes.c_int64),
+                ("per_offset", ctypes.c_int32 * 343), ("status", ctypes.c_int32)]
+
+
+COUNTS_BYTES = ctypes.sizeof(ScCounts)
+
+
+class ScError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def load(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Load libsc.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(f"{LIB_PATH} has not been built")
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    sig = {
+        "sc_hash_bytes": (sz, [i64]),
+        "sc_hash_build": (i32, [vp, i64, vp, sz, vp, vp]),
+        "sc_hash_lookup": (i32, [vp, i64, vp, i64, vp, vp]),
+        "sc_out_bound": (i64, [i64, i32, i32, i32]),
+        "sc_kmap_bytes": (sz, [i64, i32, i32, i32]),
+        "sc_kmap_scratch_bytes": (sz, [i64, i32, i32, i32]),
+        "sc_kmap_build": (i32, [vp, i64, vp, i32, i32, i32, vp, vp, sz, vp, sz, vp, vp]),
+        "sc_conv_workspace_bytes": (sz, [i32, i32, i32, i32]),
+        "sc_conv_fwd": (i32, [vp, i64, vp, vp, i64, vp, sz, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
+        "sc_counts_read": (i32, [vp, ctypes.POINTER(ScCounts), vp, i64, i32, i32, i32, vp]),
+        "sc_kmap_export": (i32, [vp, i64, i32, i32, i32, ctypes.POINTER(ScCounts), vp, vp, vp, vp]),
+        "sc_strerror": (ctypes.c_char_p, [i32]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().sc_strerror(code).decode()
+
+
+def _check(code: int, what: str):
+    if code != SC_OK:
+        raise ScError(code, what)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
+# ---- the calls of sc.h, same names ----------------------------------------------------------
+def sc_hash_bytes(n: int) -> int:
+    return load().sc_hash_bytes(n)
+
+
+def sc_out_bound(n: int, K: int, stride: int, mode) -> int:
+    return load().sc_out_bound(n, K, stride, MODES[mode])
+
+
+def sc_kmap_bytes(n: int, K: int, stride: int, mode) -> int:
+    return load().sc_kmap_bytes(n, K, stride, MODES[mode])
+
+
+def sc_kmap_scratch_bytes(n: int, K: int, stride: int, mode) -> int:
+    return load().sc_kmap_scratch_bytes(n, K, stride, MODES[mode])
+
+
+def sc_conv_workspace_bytes(K: int, C_in: int, C_out: int, dtype) -> int:
+    return load().sc_conv_workspace_bytes(K, C_in, C_out, DTYPES[dtype])
+
+
+def sc_hash_build(coords, table, counts, stream=None):
+    """coords int32 [n,4] (device), table uint8 [>= sc_hash_bytes(n)], counts uint8 [COUNTS_BYTES]."""
+    n = coords.shape[0]
+    _check(load().sc_hash_build(_ptr(coords), n, _ptr(table), table.numel() * table.element_size(),
+                                _ptr(counts), _stream(stream)), "sc_hash_build")
+
+
+def sc_hash_lookup(table, n_table, query, rows, stream=None):
+    _check(load().sc_hash_lookup(_ptr(table), n_table, _ptr(query), query.shape[0], _ptr(rows),
+                                 _stream(stream)), "sc_hash_lookup")
+
+
+def sc_kmap_build(coords, table, K, stride, mode, out_coords, kmap, scratch, counts, stream=None):
+    n = coords.shape[0]
+    _check(load().sc_kmap_build(_ptr(coords), n, _ptr(table), K, stride, MODES[mode], _ptr(out_coords),
+                                _ptr(kmap), kmap.numel() * kmap.element_size(),
+                                _ptr(scratch), 0 if scratch is None else scratch.numel() * scratch.element_size(),
+                                _ptr(counts), _stream(stream)), "sc_kmap_build")
+
+
+def sc_conv_fwd(feat_in, weight, feat_out, kmap, counts, K, stride, mode, workspace=None, stream=None):
+    """feat_in [n_in,C_in], weight [K^3,C_in,C_out] (same dtype), feat_out [n_out_cap,C_out]."""
+    n_in, C_in = feat_in.shape
+    n_out_cap, C_out = feat_out.shape
+    if tuple(weight.shape) != (K ** 3, C_in, C_out) or weight.dtype != feat_in.dtype:
+        raise ValueError("weight must be [K^3, C_in, C_out] in the feature dtype")
+    _check(load().sc_conv_fwd(_ptr(feat_in), n_in, _ptr(weight), _ptr(feat_out), n_out_cap, _ptr(kmap),
+                              kmap.numel() * kmap.element_size(), _ptr(counts), K, stride, MODES[mode],
+                              C_in, C_out, DTYPES[feat_in.dtype], DTYPES[feat_out.dtype], _ptr(workspace),
+                              0 if workspace is None else workspace.numel() * workspace.element_size(),
+                              _stream(stream)), "sc_conv_fwd")
+
+
+def sc_counts_read(counts, kmap=None, n=0, K=1, stride=1, mode="subm", stream=None, check=True) -> ScCounts:
+    h = ScCounts()
+    rc = load().sc_counts_read(_ptr(counts), ctypes.byref(h), _ptr(kmap), n, K, stride, MODES[mode], _stream(stream))
+    if check:
+        _check(rc, "sc_counts_read")
+    return h
+
+
+def sc_kmap_export(kmap, n, K, stride, mode, h_counts: ScCounts, stream=None):
+    """Plain rulebook of a map: (pairs_in [P], pairs_out [P], offset_start [K^3+1]) int32 device tensors."""
+    dev = kmap.device
+    P = int(h_counts.n_pairs)
+    pin = torch.empty(max(P, 1), dtype=torch.int32, device=dev)
+    pout = torch.empty(max(P, 1), dtype=torch.int32, device=dev)
+    ost = torch.empty(K ** 3 + 1, dtype=torch.int32, device=dev)
+    _check(load().sc_kmap_export(_ptr(kmap), n, K, stride, MODES[mode], ctypes.byref(h_counts), _ptr(pin), _ptr(pout),
+                                 _ptr(ost), _stream(stream)), "sc_kmap_export")
+    return pin[:P], pout[:P], ost
+
+
+# ---- buffers for one layer -------------------------------------------------------------------
+class LayerBuffers:
+    """All device buffers one layer needs, allocated once (torch tensors), plus the three calls
+    in order.  Holds no arithmetic: it sizes buffers with the library's own *_bytes calls."""
+
+    def __init__(self, n: int, K: int, stride: int, mode, C_in: int, C_out: int, dtype, out_dtype=None,
+                 device="cuda:0"):
+        self.n, self.K, self.stride, self.mode = n, K, stride, MODES[mode]
+        self.C_in, self.C_out = C_in, C_out
+        self.dtype = TORCH_DTYPES[DTYPES[dtype]]
+        self.out_dtype = self.dtype if out_dtype is None else TORCH_DTYPES[DTYPES[out_dtype]]
+        self.bound = sc_out_bound(n, K, stride, mode)
+        if self.bound < 0:
+            raise ScError(SC_EINVAL, "sc_out_bound")
+        u8 = dict(dtype=torch.uint8, device=device)
+        self.table = torch.empty(max(sc_hash_bytes(n), 16), **u8)
+        self.kmap = torch.empty(max(sc_kmap_bytes(n, K, stride, mode), 16), **u8)
+        self.scratch = torch.empty(max(sc_kmap_scratch_bytes(n, K, stride, mode), 16), **u8)
+        self.workspace = torch.empty(max(sc_conv_workspace_bytes(K, C_in, C_out, dtype), 16), **u8)
+        self.counts = torch.zeros(COUNTS_BYTES + 8, **u8)
+        self.out_coords = torch.empty((max(self.bound, 1), 4), dtype=torch.int32, device=device)
+        self.feat_out = torch.empty((max(self.bound, 1), C_out), dtype=self.out_dtype, device=device)
+
+    def hash_build(self, coords, stream=None):
+        sc_hash_build(coords, self.table, self.counts, stream)
+
+    def kmap_build(self, coords, stream=None):
+        sc_kmap_build(coords, self.table, self.K, self.stride, self.mode, self.out_coords, self.kmap,
+                      self.scratch, self.counts, stream)
+
+    def conv_fwd(self, feat_in, weight, stream=None):
+        sc_conv_fwd(feat_in, weight, self.feat_out, self.kmap, self.counts, self.K, self.stride, self.mode,
+                    self.workspace, stream)
+
+    def layer(self, coords, feat_in, weight, stream=None):
+        self.hash_build(coords, stream)
+        self.kmap_build(coords, stream)
+        self.conv_fwd(feat_in, weight, stream)
+
+    def read_counts(self, with_pairs=True, stream=None, check=True) -> ScCounts:
+        return sc_counts_read(self.counts, self.kmap if with_pairs else None, self.n, self.K, self.stride,
+                              self.mode, stream, check)
+
+    def export(self, h_counts=None, stream=None):
+        if h_counts is None:
+            h_counts = self.read_counts(stream=stream)
+        return sc_kmap_export(self.kmap, self.n, self.K, self.stride, self.mode, h_counts, stream)

@@ -1,0 +1,496 @@
+// Offset table / kernel map (paper Section III-C.2 for submanifold layers, Section III-B
+// eq. 1-5 and Section III-D for strided layers).
+//
+// The paper writes a dense N x K^3 table of neighbour rows (-1 where there is none) with one
+// thread per point, and for strided layers counts the distinct output cells with an atomic
+// exchange on a status table plus an atomic counter.  Here one 64-lane wavefront owns 64
+// consecutive output rows: every lane probes the location table for one row's neighbour at
+// offset k, the wavefront votes (ballot) and each lane with a hit takes the next free place in
+// the tile's list for offset k (prefix count of the vote).  No atomics, no empty entries, and a
+// layout - tile-major, grouped by offset - that lets the convolution kernel pack rows that share
+// a weight matrix into one MFMA tile and sum all offsets of a row on-chip.
+// Strided layers number their output cells in order of first occurrence (min input row per
+// cell + prefix sum), so the result is independent of thread timing, unlike an atomic counter.
+#include "sc_internal.h"
+
+namespace sc {
+
+__device__ inline uint64_t lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
+
+// Append the lanes that have `found` to the tile's list of the current offset.
+__device__ inline void compact_offset(bool found, uint32_t value, uint32_t* __restrict__ en, uint32_t& base) {
+    const uint64_t vote = __ballot(found);
+    if (found) en[base + (uint32_t)__popcll(vote & lanemask_lt())] = value;
+    base += (uint32_t)__popcll(vote);
+}
+
+__global__ void __launch_bounds__(64)
+k_kmap_header(KmapHeader* hdr, KmapHeader value) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *hdr = value;
+}
+
+__global__ void __launch_bounds__(64)
+k_set_n_out(sc_counts* counts, int64_t n_out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) counts->n_out = n_out;
+}
+
+// Submanifold: output row = input row.  One wavefront per tile.
+template <int KT>   // KT = 3: unrolled; KT = 0: any odd K at run time
+__global__ void __launch_bounds__(64)
+k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint64_t* __restrict__ keys,
+            const int32_t* __restrict__ vals, uint32_t mask, int Krt, uint16_t* __restrict__ start,
+            uint32_t* __restrict__ entries, int sstride, sc_counts* counts) {
+    const int K = KT ? KT : Krt;
+    const int K3 = K * K * K;
+    const int pad = (K - 1) / 2;
+    const int lane = threadIdx.x;
+    const int64_t tile = blockIdx.x;
+    const int64_t row = tile * TILE + lane;
+    const bool valid = row < n;
+    int4 c = make_int4(0, 0, 0, 0);
+    if (valid) c = coords[row];
+    uint16_t* st = start + tile * sstride;
+    uint32_t* en = entries + tile * (int64_t)(TILE * K3);
+    if (tile == 0 && lane == 0) counts->n_out = n;
+
+    uint32_t base = 0;
+    int k = 0;
+    for (int dx = -pad; dx <= pad; ++dx) {
+        for (int dy = -pad; dy <= pad; ++dy) {
+            for (int dz = -pad; dz <= pad; ++dz, ++k) {
+                int32_t j = -1;
+                if (valid) {
+                    if (dx == 0 && dy == 0 && dz == 0) {
+                        j = (int32_t)row;                       // the centre offset is the identity
+                    } else {
+                        const int x = c.y + dx, y = c.z + dy, z = c.w + dz;
+                        if (in_domain(x) && in_domain(y) && in_domain(z))
+                            j = table_find(keys, vals, mask, pack_key(c.x, x, y, z));
+                    }
+                }
+                if (lane == 0) st[k] = (uint16_t)base;
+                compact_offset(j >= 0, (uint32_t)j | ((uint32_t)lane << ENTRY_ROW_BITS), en, base);
+            }
+        }
+    }
+    if (lane == 0) st[K3] = (uint16_t)base;
+}
+
+// ---- strided layers with K == stride ---------------------------------------------------------
+// scratch: output-cell hash (keys, vals = min input row per cell), slot_of[n], flag words,
+// in-block word prefix, block sums / prefixes, and a dense offset table oft[bound][K3].
+struct StridedScratch {
+    uint64_t* okeys;
+    int32_t* ovals;
+    uint32_t omask;
+    int32_t* slot_of;        // [n]
+    uint64_t* flagword;      // [ceil(n/64)]  bit i%64 set iff input i is the first of its cell
+    int32_t* word_prefix;    // [ceil(n/64)]  flags before this word inside its 1024-block
+    int32_t* block_sum;      // [nblk]
+    int32_t* block_prefix;   // [nblk]
+    int32_t* oft;            // [bound][K3]
+    size_t bytes;
+};
+inline StridedScratch strided_scratch(void* p, int64_t n, int K) {
+    StridedScratch s;
+    const uint64_t cap = hash_capacity(n);
+    const int64_t words = (n + 63) / 64, nblk = (n + 1023) / 1024;
+    const int K3 = K * K * K;
+    size_t off = 0;
+    char* b = (char*)p;
+    s.okeys = (uint64_t*)(b + off); off = align_up(off + cap * 8, 256);
+    s.ovals = (int32_t*)(b + off); off = align_up(off + cap * 4, 256);
+    s.omask = (uint32_t)(cap - 1);
+    s.slot_of = (int32_t*)(b + off); off = align_up(off + (size_t)n * 4, 256);
+    s.flagword = (uint64_t*)(b + off); off = align_up(off + (size_t)words * 8, 256);
+    s.word_prefix = (int32_t*)(b + off); off = align_up(off + (size_t)words * 4, 256);
+    s.block_sum = (int32_t*)(b + off); off = align_up(off + (size_t)nblk * 4, 256);
+    s.block_prefix = (int32_t*)(b + off); off = align_up(off + (size_t)nblk * 4, 256);
+    s.oft = (int32_t*)(b + off); off = align_up(off + (size_t)n * K3 * 4, 256);
+    s.bytes = off + 256;
+    return s;
+}
+
+__global__ void __launch_bounds__(256)
+k_fill_i32(int32_t* __restrict__ p, int64_t count, int32_t v) {   // count is a multiple of 4
+    int4* p4 = reinterpret_cast<int4*>(p);
+    const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count / 4; i += nthr)
+        p4[i] = make_int4(v, v, v, v);
+}
+
+// Each input claims (or finds) the slot of its output cell floor(p/s) (eq. 2, eq. 4) and
+// lowers the slot's value to its own row index.
+__global__ void __launch_bounds__(256)
+k_strided_insert(const int4* __restrict__ coords, int64_t n, int s, uint64_t* okeys, int32_t* ovals,
+                 uint32_t omask, int32_t* __restrict__ slot_of, sc_counts* counts) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int4 c = coords[i];
+    int32_t myslot = -1;
+    if (!in_domain4(c.x, c.y, c.z, c.w)) {
+        latch_status(counts, SC_ERANGE);
+    } else {
+        const uint64_t key = pack_key(c.x, c.y / s, c.z / s, c.w / s);
+        uint32_t slot = home_slot(key, omask);
+        for (uint32_t step = 0; step <= omask; ++step) {
+            uint64_t cur = __hip_atomic_load(&okeys[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (cur == KEY_EMPTY)
+                cur = atomicCAS((unsigned long long*)&okeys[slot], (unsigned long long)KEY_EMPTY,
+                                (unsigned long long)key);
+            if (cur == KEY_EMPTY || cur == key) {
+                myslot = (int32_t)slot;
+                break;
+            }
+            slot = (slot + 1) & omask;
+        }
+        if (myslot >= 0) atomicMin(&ovals[myslot], (int32_t)i);
+        else latch_status(counts, SC_EFULL);
+    }
+    slot_of[i] = myslot;
+}
+
+// flag(i) = input i is the first (lowest row) of its cell; one bit per input, plus the
+// exclusive prefix of the flag counts of the 16 words of each 1024-input block.
+__global__ void __launch_bounds__(1024)
+k_strided_flags(int64_t n, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ ovals,
+                uint64_t* __restrict__ flagword, int32_t* __restrict__ word_prefix,
+                int32_t* __restrict__ block_sum) {
+    __shared__ int32_t wave_count[16];
+    const int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    bool first = false;
+    if (i < n) {
+        const int32_t sl = slot_of[i];
+        first = sl >= 0 && ovals[sl] == (int32_t)i;
+    }
+    const uint64_t vote = __ballot(first);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane == 0) wave_count[wave] = __popcll(vote);
+    __syncthreads();
+    if (lane == 0) {
+        int32_t before = 0;
+        for (int w = 0; w < wave; ++w) before += wave_count[w];
+        const int64_t word = (int64_t)blockIdx.x * 16 + wave;
+        if (word * 64 < n) {
+            flagword[word] = vote;
+            word_prefix[word] = before;
+        }
+        if (wave == 15) block_sum[blockIdx.x] = before + wave_count[15];
+    }
+}
+
+// Exclusive prefix of the block sums (one workgroup walks the array), total -> counts->n_out.
+__global__ void __launch_bounds__(1024)
+k_scan_blocks(const int32_t* __restrict__ block_sum, int32_t* __restrict__ block_prefix, int64_t nblk,
+              sc_counts* counts) {
+    __shared__ int32_t part[1024];
+    __shared__ int32_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < nblk; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int32_t v = i < nblk ? block_sum[i] : 0;
+        part[threadIdx.x] = v;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {           // Hillis-Steele inclusive scan
+            int32_t add = threadIdx.x >= (unsigned)off ? part[threadIdx.x - off] : 0;
+            __syncthreads();
+            part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int32_t carry = carry_s;
+        if (i < nblk) block_prefix[i] = carry + part[threadIdx.x] - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) carry_s = carry + part[1023];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) counts->n_out = carry_s;
+}
+
+// Every input finds its output row (rank of its cell's first input among all first inputs),
+// its in-cell offset (eq. 3) and kernel offset (eq. 5), and records itself in the dense table.
+__global__ void __launch_bounds__(256)
+k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
+                const int32_t* __restrict__ slot_of, const int32_t* __restrict__ ovals,
+                const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
+                const int32_t* __restrict__ block_prefix, int32_t* oft, int4* __restrict__ out_coords,
+                sc_counts* counts) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t sl = slot_of[i];
+    if (sl < 0) return;
+    const int32_t r = ovals[sl];                               // first input of this cell
+    const int32_t o = block_prefix[r >> 10] + word_prefix[r >> 6] +
+                      __popcll(flagword[r >> 6] & ((1ull << (r & 63)) - 1ull));
+    const int4 c = coords[i];
+    const int qx = c.y / s, qy = c.z / s, qz = c.w / s;
+    const int k = ((c.y - qx * s) * s + (c.z - qy * s)) * s + (c.w - qz * s);
+    const int32_t old = atomicExch(&oft[(int64_t)o * K3 + k], (int32_t)i);
+    if (old != -1) latch_status(counts, SC_EDUP);
+    if (r == (int32_t)i) out_coords[o] = make_int4(c.x, qx, qy, qz);
+}
+
+// Dense offset table -> tile-major lists.  One wavefront per output tile.
+__global__ void __launch_bounds__(64)
+k_kmap_from_oft(const int32_t* __restrict__ oft, int K3, const sc_counts* __restrict__ counts,
+                uint16_t* __restrict__ start, uint32_t* __restrict__ entries, int sstride) {
+    const int lane = threadIdx.x;
+    const int64_t tile = blockIdx.x;
+    const int64_t row = tile * TILE + lane;
+    const bool valid = row < counts->n_out;
+    uint16_t* st = start + tile * sstride;
+    uint32_t* en = entries + tile * (int64_t)(TILE * K3);
+    uint32_t base = 0;
+    for (int k = 0; k < K3; ++k) {
+        int32_t j = -1;
+        if (valid) j = oft[row * K3 + k];
+        if (lane == 0) st[k] = (uint16_t)base;
+        compact_offset(j >= 0, (uint32_t)j | ((uint32_t)lane << ENTRY_ROW_BITS), en, base);
+    }
+    if (lane == 0) st[K3] = (uint16_t)base;
+}
+
+// ---- reading a map back -----------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+k_counts_clear_pairs(sc_counts* counts) {
+    for (int i = threadIdx.x; i < 343; i += blockDim.x) counts->per_offset[i] = 0;
+    if (threadIdx.x == 0) counts->n_pairs = 0;
+}
+
+__global__ void __launch_bounds__(256)
+k_count_pairs(const uint16_t* __restrict__ start, int sstride, int K3, int64_t tiles_bound, sc_counts* counts) {
+    __shared__ int32_t hist[343];
+    for (int i = threadIdx.x; i < K3; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+    int64_t tiles = (counts->n_out + TILE - 1) / TILE;
+    if (tiles > tiles_bound) tiles = tiles_bound;
+    const int64_t items = tiles * K3;
+    const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; it < items; it += nthr) {
+        const int64_t t = it / K3;
+        const int k = (int)(it - t * K3);
+        const uint16_t* st = start + t * sstride;
+        const int c = (int)st[k + 1] - (int)st[k];
+        if (c) atomicAdd(&hist[k], c);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < K3; i += blockDim.x) {
+        if (hist[i]) {
+            atomicAdd(&counts->per_offset[i], hist[i]);
+            atomicAdd((unsigned long long*)&counts->n_pairs, (unsigned long long)hist[i]);
+        }
+    }
+}
+
+// One workgroup per offset k walks the tiles in order and copies each tile's pairs of offset k
+// behind those of the tiles before it: pairs come out ordered by output row.
+__global__ void __launch_bounds__(256)
+k_export(const uint16_t* __restrict__ start, const uint32_t* __restrict__ entries, int sstride, int K3,
+         int64_t tiles, const int32_t* __restrict__ offset_start, int32_t* __restrict__ pairs_in,
+         int32_t* __restrict__ pairs_out) {
+    __shared__ int32_t scan[256];
+    __shared__ int32_t carry_s;
+    const int k = blockIdx.x;
+    if (threadIdx.x == 0) carry_s = offset_start[k];
+    __syncthreads();
+    for (int64_t base = 0; base < tiles; base += 256) {
+        const int64_t t = base + threadIdx.x;
+        int s0 = 0, cnt = 0;
+        if (t < tiles) {
+            const uint16_t* st = start + t * sstride;
+            s0 = st[k];
+            cnt = (int)st[k + 1] - s0;
+        }
+        scan[threadIdx.x] = cnt;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {
+            int32_t add = threadIdx.x >= (unsigned)off ? scan[threadIdx.x - off] : 0;
+            __syncthreads();
+            scan[threadIdx.x] += add;
+            __syncthreads();
+        }
+        const int32_t carry = carry_s;
+        int32_t dst = carry + scan[threadIdx.x] - cnt;
+        const uint32_t* en = entries + t * (int64_t)(TILE * K3) + s0;
+        for (int e = 0; e < cnt; ++e) {
+            const uint32_t v = en[e];
+            pairs_in[dst + e] = (int32_t)(v & ENTRY_ROW_MASK);
+            pairs_out[dst + e] = (int32_t)(t * TILE + (v >> ENTRY_ROW_BITS));
+        }
+        __syncthreads();
+        if (threadIdx.x == 255) carry_s = carry + scan[255];
+        __syncthreads();
+    }
+}
+
+struct StartArg {
+    int32_t v[344];
+};
+__global__ void __launch_bounds__(256)
+k_write_starts(StartArg a, int count, int32_t* __restrict__ dst) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = a.v[i];
+}
+
+static bool kmap_args_ok(int64_t n, int K, int stride, int mode) {
+    if (n < 0 || n > SC_N_MAX || K < 1 || K > SC_K_MAX) return false;
+    if (mode == SC_SUBM) return stride == 1 && (K % 2) == 1;
+    if (mode == SC_STRIDED) return K == stride && K >= 2 && K <= 4;
+    return false;
+}
+
+}  // namespace sc
+
+using namespace sc;
+
+extern "C" int64_t sc_out_bound(int64_t n, int K, int stride, int mode) {
+    if (!kmap_args_ok(n, K, stride, mode)) return -1;
+    return n;
+}
+
+extern "C" size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode) {
+    if (!kmap_args_ok(n, K, stride, mode)) return 0;
+    return kmap_layout(sc_out_bound(n, K, stride, mode), K).bytes;
+}
+
+extern "C" size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode) {
+    if (!kmap_args_ok(n, K, stride, mode)) return 0;
+    if (mode == SC_SUBM) return 256;
+    return strided_scratch(nullptr, n, K).bytes;
+}
+
+extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
+                             int32_t* d_out_coords, void* d_kmap, size_t kmap_bytes, void* d_scratch,
+                             size_t scratch_bytes, sc_counts* d_counts, void* stream) {
+    if (!kmap_args_ok(n, K, stride, mode)) return SC_EINVAL;
+    if (d_kmap == nullptr || d_counts == nullptr || (n > 0 && d_coords == nullptr)) return SC_EINVAL;
+    if (!aligned16(d_coords) || !aligned16(d_kmap) || !aligned16(d_counts) || !aligned16(d_out_coords) ||
+        !aligned16(d_scratch) || !aligned16(d_table))
+        return SC_EINVAL;
+    if (mode == SC_SUBM && d_table == nullptr) return SC_EINVAL;
+    if (mode == SC_STRIDED && (d_out_coords == nullptr || d_scratch == nullptr)) return SC_EINVAL;
+    if (kmap_bytes < sc_kmap_bytes(n, K, stride, mode)) return SC_ECAP;
+    if (scratch_bytes < sc_kmap_scratch_bytes(n, K, stride, mode) && mode == SC_STRIDED) return SC_ECAP;
+
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t bound = sc_out_bound(n, K, stride, mode);
+    const KmapLayout L = kmap_layout(bound, K);
+    uint16_t* start = (uint16_t*)((char*)d_kmap + L.off_start);
+    uint32_t* entries = (uint32_t*)((char*)d_kmap + L.off_entries);
+    KmapHeader h{};
+    h.magic = KMAP_MAGIC; h.K = K; h.stride = stride; h.mode = mode;
+    h.n_in = n; h.n_out_bound = bound; h.tiles = L.tiles; h.sstride = L.sstride;
+    hipLaunchKernelGGL(k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap, h);
+    SC_HIP_CHECK_LAUNCH();
+
+    if (mode == SC_SUBM) {
+        HashTable t = table_view(const_cast<void*>(d_table), n);
+        if (n == 0) {
+            hipLaunchKernelGGL(k_set_n_out, dim3(1), dim3(64), 0, s, d_counts, (int64_t)0);
+            SC_HIP_CHECK_LAUNCH();
+            return SC_OK;
+        }
+        if (K == 3)
+            hipLaunchKernelGGL(k_kmap_subm<3>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
+                               (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, K, start, entries,
+                               L.sstride, d_counts);
+        else
+            hipLaunchKernelGGL(k_kmap_subm<0>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
+                               (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, K, start, entries,
+                               L.sstride, d_counts);
+        SC_HIP_CHECK_LAUNCH();
+        if (d_out_coords != nullptr && d_out_coords != d_coords) {
+            if (hipMemcpyAsync(d_out_coords, d_coords, (size_t)n * 16, hipMemcpyDeviceToDevice, s) != hipSuccess)
+                return SC_EHIP;
+        }
+        return SC_OK;
+    }
+
+    // strided, K == stride
+    StridedScratch sc_ = strided_scratch(d_scratch, n, K);
+    const uint64_t cap = (uint64_t)sc_.omask + 1;
+    if (int rc = launch_table_fill(sc_.okeys, sc_.ovals, cap, 1, 0x7fffffff, nullptr, 0, s)) return rc;
+    const int64_t oft_count = (int64_t)align_up((size_t)n * L.K3, 4);
+    if (oft_count > 0) {
+        unsigned ob = (unsigned)((oft_count / 4 + 255) / 256);
+        if (ob > 4096) ob = 4096;
+        hipLaunchKernelGGL(k_fill_i32, dim3(ob), dim3(256), 0, s, sc_.oft, oft_count, -1);
+        SC_HIP_CHECK_LAUNCH();
+    }
+    const int64_t nblk = (n + 1023) / 1024;
+    if (n > 0) {
+        const unsigned gb = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, sc_.okeys,
+                           sc_.ovals, sc_.omask, sc_.slot_of, d_counts);
+        SC_HIP_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n, (const int32_t*)sc_.slot_of,
+                           (const int32_t*)sc_.ovals, sc_.flagword, sc_.word_prefix, sc_.block_sum);
+        SC_HIP_CHECK_LAUNCH();
+    }
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum, sc_.block_prefix, nblk,
+                       d_counts);
+    SC_HIP_CHECK_LAUNCH();
+    if (n > 0) {
+        const unsigned gb = (unsigned)((n + 255) / 256);
+        hipLaunchKernelGGL(k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
+                           (const int32_t*)sc_.slot_of, (const int32_t*)sc_.ovals, (const uint64_t*)sc_.flagword,
+                           (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, sc_.oft,
+                           (int4*)d_out_coords, d_counts);
+        SC_HIP_CHECK_LAUNCH();
+        hipLaunchKernelGGL(k_kmap_from_oft, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int32_t*)sc_.oft, L.K3,
+                           (const sc_counts*)d_counts, start, entries, L.sstride);
+        SC_HIP_CHECK_LAUNCH();
+    }
+    return SC_OK;
+}
+
+extern "C" int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts, const void* d_kmap, int64_t n, int K,
+                              int stride, int mode, void* stream) {
+    if (d_counts == nullptr || h_counts == nullptr) return SC_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if (d_kmap != nullptr) {
+        if (!kmap_args_ok(n, K, stride, mode)) return SC_EINVAL;
+        const KmapLayout L = kmap_layout(sc_out_bound(n, K, stride, mode), K);
+        const uint16_t* start = (const uint16_t*)((const char*)d_kmap + L.off_start);
+        hipLaunchKernelGGL(k_counts_clear_pairs, dim3(1), dim3(256), 0, s, d_counts);
+        SC_HIP_CHECK_LAUNCH();
+        if (L.tiles > 0) {
+            int64_t items = L.tiles * L.K3;
+            unsigned gb = (unsigned)((items + 255) / 256);
+            if (gb > 1024) gb = 1024;
+            hipLaunchKernelGGL(k_count_pairs, dim3(gb), dim3(256), 0, s, start, L.sstride, L.K3, L.tiles, d_counts);
+            SC_HIP_CHECK_LAUNCH();
+        }
+    }
+    if (hipMemcpyAsync(h_counts, d_counts, sizeof(sc_counts), hipMemcpyDeviceToHost, s) != hipSuccess) return SC_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return SC_EHIP;
+    return h_counts->status < 0 ? h_counts->status : SC_OK;
+}
+
+extern "C" int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, int mode, const sc_counts* h_counts,
+                              int32_t* d_pairs_in, int32_t* d_pairs_out, int32_t* d_offset_start, void* stream) {
+    if (d_kmap == nullptr || h_counts == nullptr || d_offset_start == nullptr) return SC_EINVAL;
+    if (!kmap_args_ok(n, K, stride, mode)) return SC_EINVAL;
+    if (h_counts->n_pairs > 0 && (d_pairs_in == nullptr || d_pairs_out == nullptr)) return SC_EINVAL;
+    if (h_counts->n_pairs > 0x7fffffffLL) return SC_ECAP;
+    hipStream_t s = (hipStream_t)stream;
+    const KmapLayout L = kmap_layout(sc_out_bound(n, K, stride, mode), K);
+    StartArg h_start{};
+    int32_t acc = 0;
+    for (int k = 0; k < L.K3; ++k) {
+        h_start.v[k] = acc;
+        acc += h_counts->per_offset[k];
+    }
+    h_start.v[L.K3] = acc;
+    if ((int64_t)acc != h_counts->n_pairs) return SC_EINVAL;
+    hipLaunchKernelGGL(k_write_starts, dim3(1), dim3(256), 0, s, h_start, L.K3 + 1, d_offset_start);
+    SC_HIP_CHECK_LAUNCH();
+    const int64_t tiles = (h_counts->n_out + TILE - 1) / TILE;
+    if (tiles > 0 && acc > 0) {
+        hipLaunchKernelGGL(k_export, dim3((unsigned)L.K3), dim3(256), 0, s,
+                           (const uint16_t*)((const char*)d_kmap + L.off_start),
+                           (const uint32_t*)((const char*)d_kmap + L.off_entries), L.sstride, L.K3, tiles,
+                           (const int32_t*)d_offset_start, d_pairs_in, d_pairs_out);
+        SC_HIP_CHECK_LAUNCH();
+    }
+    return SC_OK;
+}

@@ -1,0 +1,74 @@
+"""CPU tests: the C-ABI library builds, loads and exports every symbol include/sc.h declares;
+host-side argument checks and size queries (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_07710_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 10
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in sc.h but not exported by libsc.so"
+    assert sorted(binding.SYMBOLS) == names
+
+
+def test_counts_struct_layout():
+    assert ctypes.sizeof(binding.ScCounts) == 24 + 343 * 4 + 4
+    assert binding.ScCounts.per_offset.offset == 24
+    assert binding.ScCounts.status.offset == 24 + 343 * 4
+
+
+def test_size_queries(lib):
+    assert lib.sc_hash_bytes(0) == 1024 * 12
+    assert lib.sc_hash_bytes(1000) == 2048 * 12
+    assert lib.sc_hash_bytes(1024) == 2048 * 12
+    assert lib.sc_hash_bytes(1025) == 4096 * 12
+    assert lib.sc_hash_bytes(-1) == 0
+    assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
+    assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
+    assert lib.sc_out_bound(500, 2, 1, binding.SC_SUBM) == -1      # even K has no centre
+    assert lib.sc_out_bound(500, 3, 2, binding.SC_SUBM) == -1      # submanifold stride is 1
+    assert lib.sc_kmap_bytes(500, 9, 1, binding.SC_SUBM) == 0
+    # tile-major blob: header + uint16 starts + one uint32 per possible pair
+    b = lib.sc_kmap_bytes(6400, 3, 1, binding.SC_SUBM)
+    assert b >= 100 * 64 * 27 * 4 and b < 100 * 64 * 27 * 4 + 100 * 64 + 1024
+    assert lib.sc_kmap_scratch_bytes(6400, 2, 2, binding.SC_STRIDED) > 6400 * 8 * 4
+    assert lib.sc_conv_workspace_bytes(3, 64, 64, binding.SC_F16) == 27 * 64 * 64 * 2
+    assert lib.sc_conv_workspace_bytes(3, 16, 16, binding.SC_F32) == 0
+
+
+def test_host_side_argument_errors(lib):
+    # null pointers and bad shapes are rejected before anything is enqueued (no GPU needed)
+    assert lib.sc_hash_build(None, 10, None, 0, None, None) == binding.SC_EINVAL
+    assert lib.sc_hash_build(None, -1, 16, 0, 16, None) == binding.SC_EINVAL
+    assert lib.sc_hash_build(16, 10, 32, 8, 48, None) == binding.SC_ECAP
+    assert lib.sc_hash_build(17, 10, 32, 1 << 20, 48, None) == binding.SC_EINVAL      # misaligned
+    assert lib.sc_kmap_build(16, 10, 32, 2, 1, binding.SC_SUBM, None, 64, 1 << 20, None, 0, 80, None) == binding.SC_EINVAL
+    assert lib.sc_kmap_build(16, 10, 32, 3, 1, binding.SC_SUBM, None, 64, 8, None, 0, 80, None) == binding.SC_ECAP
+    assert lib.sc_kmap_build(16, 10, None, 3, 1, binding.SC_SUBM, None, 64, 1 << 20, None, 0, 80, None) == binding.SC_EINVAL
+    assert lib.sc_conv_fwd(16, 10, 32, 48, 10, 64, 1 << 20, 80, 3, 1, binding.SC_SUBM, 24, 32, binding.SC_F16,
+                           binding.SC_F16, 96, 1 << 20, None) == binding.SC_EINVAL   # C_in not 32/64/128/256
+    assert lib.sc_conv_fwd(16, 10, 32, 48, 10, 64, 1 << 20, 80, 3, 1, binding.SC_SUBM, 32, 32, binding.SC_F16,
+                           binding.SC_BF16, 96, 1 << 20, None) == binding.SC_EINVAL  # output type mismatch
+    assert lib.sc_conv_fwd(16, 10, 32, 48, 10, 64, 1 << 20, 80, 3, 1, binding.SC_SUBM, 32, 32, binding.SC_F16,
+                           binding.SC_F16, 96, 16, None) == binding.SC_ECAP          # workspace too small
+    assert binding.strerror(binding.SC_EDUP) == "duplicate input coordinate"
+    assert binding.strerror(12345) == "unknown status"

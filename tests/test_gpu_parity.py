@@ -1,0 +1,290 @@
+"""GPU tests: the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Kernel maps must be bit-exact (after the canonical sort, and - where the library promises an
+order - in that order too); outputs must agree within 1e-5 (fp32) / 2e-2 (fp16, bf16 inputs
+with fp32 accumulation) of the largest reference magnitude.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_07710_amd import binding as sc
+from paper_2402_07710_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "f16": 2e-2, "bf16": 2e-2}
+TDT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+DEV = "cuda:0"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def to_dev(x_f32: np.ndarray, dtype: str):
+    return torch.from_numpy(np.ascontiguousarray(x_f32)).to(DEV).to(TDT[dtype]).contiguous()
+
+
+def run_layer(coords, feat, weight, K, stride, mode, dtype, out_dtype=None):
+    """Whole layer on the GPU.  Returns (buffers, counts, out_coords np, feat_out np float64)."""
+    n = len(coords)
+    C_in, C_out = weight.shape[1], weight.shape[2]
+    buf = sc.LayerBuffers(n, K, stride, mode, C_in, C_out, dtype, out_dtype, device=DEV)
+    d_coords = torch.from_numpy(np.ascontiguousarray(coords, dtype=np.int32)).to(DEV).reshape(-1, 4)
+    d_feat = to_dev(feat.reshape(n, C_in), dtype)
+    d_w = to_dev(weight, dtype)
+    buf.layer(d_coords, d_feat, d_w)
+    h = buf.read_counts()
+    n_out = int(h.n_out)
+    out_coords = buf.out_coords[:n_out].cpu().numpy()
+    out = buf.feat_out[:n_out].to(torch.float64).cpu().numpy()
+    return buf, h, out_coords, out
+
+
+def exported_map(buf, h):
+    pin, pout, ost = buf.export(h)
+    return dict(pair_in=pin.cpu().numpy(), pair_out=pout.cpu().numpy(), offset_start=ost.cpu().numpy().astype(np.int64))
+
+
+def assert_maps_equal(gpu_km, out_coords, ref_km, exact_order):
+    """Bit-exact comparison of two kernel maps after canonical sorting (and without it where
+    the order is part of the contract)."""
+    g = dict(gpu_km, out_coords=out_coords)
+    assert np.array_equal(g["offset_start"], ref_km["offset_start"]), "per-offset pair counts differ"
+    oc_g, per_g = oracle.canonical_pairs(g)
+    oc_r, per_r = oracle.canonical_pairs(ref_km)
+    assert np.array_equal(oc_g, oc_r), "output coordinate sets differ"
+    for k, (a, b) in enumerate(zip(per_g, per_r)):
+        assert np.array_equal(a, b), f"pairs of offset {k} differ"
+    if exact_order:
+        assert np.array_equal(out_coords, ref_km["out_coords"])
+        assert np.array_equal(g["pair_in"], ref_km["pair_in"])
+        assert np.array_equal(g["pair_out"], ref_km["pair_out"])
+
+
+def rel_err(got, ref):
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30)) if ref.size else 0.0
+
+
+def check_layer(coords, K, stride, mode, C_in, C_out, dtype, seed=0, out_dtype=None, threads=8):
+    n = len(coords)
+    feat = synth.features(n, C_in, dtype, seed)
+    weight = synth.weights(K ** 3, C_in, C_out, dtype, seed)
+    buf, h, out_coords, out = run_layer(coords, feat, weight, K, stride, mode, dtype, out_dtype)
+    ref_km = oracle.kmap(coords, K, stride, mode)
+    assert h.n_in == n and h.n_out == ref_km["n_out"] and h.n_pairs == ref_km["offset_start"][-1]
+    assert list(h.per_offset[:K ** 3]) == list(np.diff(ref_km["offset_start"]))
+    assert_maps_equal(exported_map(buf, h), out_coords, ref_km, exact_order=True)
+    ref = oracle.conv(feat, weight, ref_km, threads=threads)
+    err = rel_err(out, ref)
+    assert err <= TOL[dtype], f"max relative error {err:.3e} > {TOL[dtype]}"
+    return err
+
+
+# ---- location table --------------------------------------------------------------------------
+@pytest.mark.parametrize("n,grid", [(1, 4), (63, 8), (2000, 64), (50000, 64)])
+def test_hash_finds_every_key(n, grid):
+    say(f"hash n={n} grid={grid}")
+    coords = synth.uniform_cells(n, grid, seed=n)
+    coords[:, 0] = np.arange(n) % 3
+    d_coords = torch.from_numpy(coords).to(DEV)
+    table = torch.empty(sc.sc_hash_bytes(n), dtype=torch.uint8, device=DEV)
+    counts = torch.zeros(sc.COUNTS_BYTES + 8, dtype=torch.uint8, device=DEV)
+    sc.sc_hash_build(d_coords, table, counts)
+    h = sc.sc_counts_read(counts)
+    assert h.n_in == n and h.status == 0
+    rows = torch.empty(n, dtype=torch.int32, device=DEV)
+    sc.sc_hash_lookup(table, n, d_coords, rows)
+    assert torch.equal(rows.cpu(), torch.arange(n, dtype=torch.int32))
+    # absent keys: same cells in a batch slot that is not used, and shifted cells
+    absent = coords.copy()
+    absent[:, 0] = 7
+    rows2 = torch.empty(n, dtype=torch.int32, device=DEV)
+    sc.sc_hash_lookup(table, n, torch.from_numpy(absent).to(DEV), rows2)
+    assert bool((rows2 == -1).all())
+    present = {tuple(r) for r in coords.tolist()}
+    shifted = coords.copy()
+    shifted[:, 3] += 1
+    want = np.array([-1 if tuple(r) not in present else 0 for r in shifted.tolist()])
+    sc.sc_hash_lookup(table, n, torch.from_numpy(shifted).to(DEV), rows2)
+    got = rows2.cpu().numpy()
+    assert np.array_equal(got == -1, want == -1)
+    hit = got >= 0
+    assert np.array_equal(coords[got[hit]], shifted[hit])
+
+
+def test_hash_reports_duplicates_and_range():
+    say("hash errors")
+    coords = synth.uniform_cells(500, 16, seed=1)
+    dup = coords.copy()
+    dup[400] = dup[17]
+    table = torch.empty(sc.sc_hash_bytes(500), dtype=torch.uint8, device=DEV)
+    counts = torch.zeros(sc.COUNTS_BYTES + 8, dtype=torch.uint8, device=DEV)
+    sc.sc_hash_build(torch.from_numpy(dup).to(DEV), table, counts)
+    assert sc.sc_counts_read(counts, check=False).status == sc.SC_EDUP
+    bad = coords.copy()
+    bad[3, 2] = 65535
+    sc.sc_hash_build(torch.from_numpy(bad).to(DEV), table, counts)
+    assert sc.sc_counts_read(counts, check=False).status == sc.SC_ERANGE
+    bad[3, 2] = -1
+    sc.sc_hash_build(torch.from_numpy(bad).to(DEV), table, counts)
+    assert sc.sc_counts_read(counts, check=False).status == sc.SC_ERANGE
+    # a clean build clears the latch
+    sc.sc_hash_build(torch.from_numpy(coords).to(DEV), table, counts)
+    assert sc.sc_counts_read(counts).status == 0
+
+
+# ---- whole layers, small: several tiles and a ragged tail --------------------------------------
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 127, 128, 129, 1000])
+@pytest.mark.parametrize("dtype,C", [("f32", 16), ("f16", 32)])
+def test_subm_tile_edges(n, dtype, C):
+    say(f"subm edges n={n} {dtype}")
+    coords = synth.uniform_cells(n, 6 if n < 200 else 12, seed=n)
+    check_layer(coords, 3, 1, "subm", C, C, dtype, seed=n)
+
+
+@pytest.mark.parametrize("K,s", [(2, 2), (3, 3), (4, 4)])
+@pytest.mark.parametrize("n", [1, 64, 65, 700])
+def test_strided_small(K, s, n):
+    say(f"strided K={K} n={n}")
+    coords = synth.uniform_cells(n, 10, seed=100 + n)
+    coords[:, 0] = np.arange(n) % 2
+    check_layer(coords, K, s, "strided", 32, 64, "f16", seed=n)
+    check_layer(coords, K, s, "strided", 8, 24, "f32", seed=n)
+
+
+@pytest.mark.parametrize("K", [1, 5, 7])
+def test_subm_other_kernel_sizes(K):
+    say(f"subm K={K}")
+    coords = synth.uniform_cells(900, 10, seed=K)
+    check_layer(coords, K, 1, "subm", 32, 16, "bf16", seed=K)
+    check_layer(coords[:300], K, 1, "subm", 5, 7, "f32", seed=K)
+
+
+@pytest.mark.parametrize("dtype,C_in,C_out", [("f16", 32, 32), ("f16", 64, 64), ("f16", 128, 128), ("f16", 256, 48),
+                                              ("bf16", 64, 64), ("bf16", 32, 256), ("bf16", 128, 16),
+                                              ("f32", 16, 16), ("f32", 3, 100), ("f32", 70, 130)])
+def test_channel_shapes(dtype, C_in, C_out):
+    say(f"channels {dtype} {C_in}->{C_out}")
+    coords = synth.uniform_cells(3000, 18, seed=C_in + C_out)     # about half the cells active: ~14 pairs/voxel
+    coords[:, 0] = np.arange(len(coords)) % 2
+    check_layer(coords, 3, 1, "subm", C_in, C_out, dtype, seed=1)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_fp32_output_of_16bit_layer(dtype):
+    say(f"fp32 output {dtype}")
+    coords = synth.uniform_cells(2000, 14, seed=9)
+    err = check_layer(coords, 3, 1, "subm", 64, 32, dtype, seed=2, out_dtype="f32")
+    assert err < 1e-5        # 16-bit inputs are exact in fp32; only the summation order differs
+
+
+def test_empty_input():
+    say("empty")
+    coords = np.zeros((0, 4), np.int32)
+    for mode, K, s in (("subm", 3, 1), ("strided", 2, 2)):
+        buf = sc.LayerBuffers(0, K, s, mode, 32, 32, "f16", device=DEV)
+        d_coords = torch.zeros((0, 4), dtype=torch.int32, device=DEV)
+        buf.layer(d_coords, torch.zeros((0, 32), dtype=torch.float16, device=DEV),
+                  torch.zeros((K ** 3, 32, 32), dtype=torch.float16, device=DEV))
+        h = buf.read_counts()
+        assert h.n_in == 0 and h.n_out == 0 and h.n_pairs == 0 and h.status == 0
+
+
+def test_domain_edges_and_batches():
+    """Voxels on the faces of the key domain: probes that leave it must miss, not wrap."""
+    say("domain edges")
+    m = sc.SC_COORD_MAX if hasattr(sc, "SC_COORD_MAX") else 65534
+    pts = []
+    for b in (0, 5, m):
+        for x in (0, 1, m - 1, m):
+            for y in (0, m):
+                for z in (0, 1, m):
+                    pts.append((b, x, y, z))
+    coords = np.array(pts, dtype=np.int32)
+    check_layer(coords, 3, 1, "subm", 32, 32, "f16", seed=3)
+    check_layer(coords, 5, 1, "subm", 4, 4, "f32", seed=3)
+    check_layer(coords, 2, 2, "strided", 32, 32, "bf16", seed=3)
+
+
+def test_strided_reports_duplicates():
+    say("strided dup")
+    coords = synth.uniform_cells(300, 8, seed=2)
+    coords[200] = coords[5]
+    buf = sc.LayerBuffers(300, 2, 2, "strided", 32, 32, "f16", device=DEV)
+    d = torch.from_numpy(coords).to(DEV)
+    buf.hash_build(d)
+    buf.kmap_build(d)
+    assert buf.read_counts(check=False).status == sc.SC_EDUP
+
+
+def test_maps_are_reproducible_bit_for_bit():
+    """The same input gives the same kernel-map bytes and the same output coordinates on every
+    run (no dependence on thread timing)."""
+    say("determinism")
+    coords = synth.lidar_scene(1)[:30000]
+    d = torch.from_numpy(coords).to(DEV)
+    for mode, K, s in (("subm", 3, 1), ("strided", 2, 2)):
+        buf = sc.LayerBuffers(len(coords), K, s, mode, 32, 32, "f16", device=DEV)
+        ref = None
+        for _ in range(5):
+            buf.kmap.zero_()
+            buf.hash_build(d)
+            buf.kmap_build(d)
+            h = buf.read_counts()
+            pin, pout, ost = buf.export(h)
+            cur = (pin.clone(), pout.clone(), ost.clone(), buf.out_coords[:h.n_out].clone())
+            if ref is None:
+                ref = cur
+            else:
+                assert all(torch.equal(a, b) for a, b in zip(ref, cur))
+
+
+def test_delta_weight_passthrough():
+    """W[centre] = I reproduces the input rows bit for bit in every dtype."""
+    say("delta weights")
+    coords = synth.uniform_cells(1500, 12, seed=4)
+    for dtype, C in (("f32", 16), ("f16", 32), ("bf16", 64)):
+        feat = synth.features(1500, C, dtype, 5)
+        W = np.zeros((27, C, C), np.float32)
+        W[13] = np.eye(C)
+        _, _, _, out = run_layer(coords, feat, W, 3, 1, "subm", dtype)
+        assert np.array_equal(out, feat.astype(np.float64))
+
+
+# ---- the five named configurations at full size ----------------------------------------------
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "target64"])
+def test_named_config_full(name):
+    say(f"config {name}")
+    cfg = synth.make_config(name)
+    err = check_layer(cfg["coords"], cfg["K"], cfg["stride"], cfg["mode"], cfg["C_in"], cfg["C_out"], cfg["dtype"],
+                      threads=16)
+    say(f"  {name}: N={len(cfg['coords'])} max rel err {err:.3e}")
+
+
+def test_cfg5_full_map_and_sampled_outputs():
+    """~1M voxels, C=128: the whole kernel map is compared; outputs are compared on a sample of
+    rows the oracle computes one by one (its triple loop over the full set takes minutes)."""
+    say("config cfg5")
+    cfg = synth.make_config("cfg5")
+    coords, feat, weight = cfg["coords"], cfg["feat"], cfg["weight"]
+    n = len(coords)
+    buf, h, out_coords, out = run_layer(coords, feat, weight, 3, 1, "subm", "f16")
+    ref_km = oracle.kmap(coords, 3, 1, "subm")
+    say(f"  cfg5: N={n} P={ref_km['offset_start'][-1]}")
+    assert h.n_pairs == ref_km["offset_start"][-1]
+    assert_maps_equal(exported_map(buf, h), out_coords, ref_km, exact_order=True)
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([rng.choice(n, 20000, replace=False), np.arange(0, 200), np.arange(n - 200, n)]))
+    keep = np.isin(ref_km["pair_out"], rows)
+    ost = np.zeros(28, np.int64)
+    for k in range(27):
+        sl = slice(ref_km["offset_start"][k], ref_km["offset_start"][k + 1])
+        ost[k + 1] = ost[k] + int(keep[sl].sum())
+    sub = dict(ref_km, pair_in=ref_km["pair_in"][keep], pair_out=ref_km["pair_out"][keep], offset_start=ost)
+    ref = oracle.conv(feat, weight, sub, threads=16)
+    err = rel_err(out[rows], ref[rows])
+    say(f"  cfg5 sampled rows {len(rows)} max rel err {err:.3e}")
+    assert err <= TOL["f16"]
