@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-convolution hot path on one MI355X.
+
+One step = one whole layer on synthetic input already resident in HBM:
+sc_hash_build -> sc_kmap_build -> sc_conv_fwd (kernel map construction included).
+Prints ONE JSON line: effective TFLOP/s over active MACs (2*P*C_in*C_out / time per layer),
+ms per layer, the per-phase split, the roofline of the kernel that takes the most time
+(durations from HIP events recorded around every kernel launch, on the launch's stream), and the
+CPU oracle timed on this host's cores for the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|target64]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_MFMA_TFLOPS = 2500.0      # dense fp16 / bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3       # fp32 vector ALU
+
+
+def algorithmic_bytes(kernel: str, st: dict) -> float | None:
+    """Bytes one launch of `kernel` has to move by the method's own accounting (per-unit figures
+    times units per launch; the design doc states both)."""
+    N, N_out, P, K3, cap = st["N"], st["N_out"], st["P"], st["K3"], st["cap"]
+    C_in, C_out, e = st["C_in"], st["C_out"], st["elem_bytes"]
+    if kernel == "k_table_fill":
+        return 8.0 * cap
+    if kernel == "k_hash_insert":
+        return N * (16 + 8 + 8 + 4)                       # coords, CAS read+write, value
+    if kernel == "k_kmap_subm":
+        hits = P - N
+        return N * 16 + N * (K3 - 1) * 8 + hits * 4 + P * 4 + (N / 64.0) * 2 * (K3 + 1)
+    if kernel in ("k_conv_mfma", "k_conv_f32"):
+        return N * C_in * e + N_out * C_out * e + K3 * C_in * C_out * e + P * 4
+    if kernel == "k_strided_insert":
+        return N * (16 + 8 + 8 + 4 + 4)
+    if kernel == "k_strided_pairs":
+        return N * (16 + 4 + 4 + 4 + 8 + 4 + 4) + N_out * 16
+    if kernel == "k_kmap_from_oft":
+        return N_out * K3 * 4 + P * 4 + (N_out / 64.0) * 2 * (K3 + 1)
+    if kernel == "k_fill_i32":
+        return N * K3 * 4.0
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (one process, one MI355X); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2402_07710_amd import binding as sc
+    from paper_2402_07710_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    sc.load(build_if_missing=True)
+
+    cfg = synth.make_config(args.workload)
+    coords, K, stride, mode = cfg["coords"], cfg["K"], cfg["stride"], cfg["mode"]
+    C_in, C_out, dtype = cfg["C_in"], cfg["C_out"], cfg["dtype"]
+    N = len(coords)
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    d_coords = torch.from_numpy(coords).to(dev)
+    d_feat = torch.from_numpy(cfg["feat"]).to(dev).to(tdt).contiguous()
+    d_w = torch.from_numpy(cfg["weight"]).to(dev).to(tdt).contiguous()
+    buf = sc.LayerBuffers(N, K, stride, mode, C_in, C_out, dtype, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        buf.hash_build(d_coords, stream)
+        buf.kmap_build(d_coords, stream)
+        buf.conv_fwd(d_feat, d_w, stream)
+
+    step()
+    h = buf.read_counts()
+    if h.status != 0:
+        raise RuntimeError(f"device status {h.status}")
+    P, N_out = int(h.n_pairs), int(h.n_out)
+    flops = 2.0 * P * C_in * C_out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-phase split with torch events (the library launches on torch's current stream)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        ev[i][0].record(stream)
+        buf.hash_build(d_coords, stream)
+        ev[i][1].record(stream)
+        buf.kmap_build(d_coords, stream)
+        ev[i][2].record(stream)
+        buf.conv_fwd(d_feat, d_w, stream)
+        ev[i][3].record(stream)
+    torch.cuda.synchronize()
+    phases = {name: float(np.median([e[j].elapsed_time(e[j + 1]) for e in ev]))
+              for j, name in enumerate(["hash_ms", "kmap_ms", "conv_ms"])}
+
+    # per-kernel durations: HIP events around every launch, recorded by the library itself on
+    # the launch stream, over the same number of steps
+    sc.sc_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    prof = sc.sc_profile_read()
+    sc.sc_profile_enable(False)
+    kernels = {name: {"launches": l, "avg_us": 1e3 * ms / l} for name, (l, ms) in prof.items()}
+    per_step_us = {name: 1e3 * ms / args.steps for name, (l, ms) in prof.items()}
+    dominant = max(per_step_us, key=per_step_us.get)
+    launches_per_step = prof[dominant][0] / args.steps
+    avg_s = prof[dominant][1] * 1e-3 / prof[dominant][0]
+    st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=sc.sc_hash_bytes(N) // 12, C_in=C_in, C_out=C_out,
+              elem_bytes=d_feat.element_size())
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+    if dominant in ("k_conv_mfma", "k_conv_f32"):
+        # the contraction: flops of the pairs that exist against the matrix-core (or fp32 ALU) peak
+        peak = PEAK_MFMA_TFLOPS if dominant == "k_conv_mfma" else PEAK_FP32_TFLOPS
+        achieved = flops / avg_s / 1e12
+        roofline = {"kernel": dominant, "bound": "mfma" if dominant == "k_conv_mfma" else "alu",
+                    "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                    "traffic": traffic, "avg_us": avg_s * 1e6,
+                    "hbm_gbs_algorithmic": algorithmic_bytes(dominant, st) / avg_s / 1e9}
+    else:
+        ab = algorithmic_bytes(dominant, st)
+        achieved = ab / avg_s / 1e9 if ab else None
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": (achieved / PEAK_HBM_GBS) if achieved else None,
+                    "traffic": traffic, "avg_us": avg_s * 1e6, "launches_per_step": launches_per_step}
+    per_kernel = {}
+    for name in kernels:
+        ab = algorithmic_bytes(name, st)
+        per_kernel[name] = {"avg_us": round(kernels[name]["avg_us"], 3),
+                            "per_step_us": round(per_step_us[name], 3)}
+        if ab:
+            per_kernel[name]["hbm_gbs_algorithmic"] = round(ab / (kernels[name]["avg_us"] * 1e-6) / 1e9, 1)
+        if name in ("k_conv_mfma", "k_conv_f32"):
+            per_kernel[name]["tflops_active"] = round(flops / (kernels[name]["avg_us"] * 1e-6) / 1e12, 2)
+
+    out = {
+        "metric": "effective TFLOP/s over active MACs, whole layer incl. kernel map (hash + kmap + conv)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "mode": mode, "K": K, "stride": stride, "C_in": C_in,
+                   "C_out": C_out, "N": N, "N_out": N_out, "P": P, "pairs_per_voxel": P / max(N, 1)},
+        "phases_ms": phases, "kernels": per_kernel, "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # the oracle as it stands, single thread, on the whole workload when that takes seconds,
+        # else on a prefix of the rows
+        n_s = N if N <= 150_000 else 150_000
+        feat64 = cfg["feat"][:n_s].astype(np.float64)
+        w64 = cfg["weight"].astype(np.float64)
+        reps = 0
+        t_cpu0 = time.perf_counter()
+        while True:
+            km = oracle.kmap(coords[:n_s], K, stride, mode)
+            oracle.conv(feat64, w64, km, threads=1)
+            reps += 1
+            if time.perf_counter() - t_cpu0 > 10.0 or reps >= 10:
+                break
+        t_cpu = (time.perf_counter() - t_cpu0) / reps
+        P_s = int(km["offset_start"][-1])
+        out["cpu_baseline"] = {
+            "value": 2.0 * P_s * C_in * C_out / t_cpu / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "ms_per_layer": t_cpu * 1e3,
+            "sample": (f"whole {args.workload} layer" if n_s == N else f"first {n_s} of {N} rows of {args.workload}")
+                      + f" (N={n_s}, P={P_s}), kernel map + convolution, {reps} repetitions, mean",
+        }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

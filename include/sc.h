@@ -15,10 +15,10 @@
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller, 16-byte aligned, and only
  *     borrowed for the duration of the stream work the call enqueues.  Pointers named h_* are
- *     host memory.  The library allocates nothing on the device and keeps no global state.
+ *     host memory.  The library allocates nothing on the device and keeps no state between
+ *     calls (the optional timing aid at the end of this file aside).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls except
- *     sc_counts_read and sc_kmap_export_host-style readers are asynchronous on that stream and
- *     never synchronise.
+ *     sc_counts_read (and sc_profile_read) are asynchronous on that stream and never synchronise.
  *   - Every function returns an int status: SC_OK or a negative SC_E* code.  Argument errors
  *     are detected on the host before anything is enqueued.  Data-dependent errors (duplicate
  *     or out-of-domain coordinates, table overflow) are latched by the kernels into
@@ -137,8 +137,8 @@ size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_in);
  *   d_kmap      blob from sc_kmap_build for the same (n_in, K, stride, mode)
  *   dtype_in    SC_F32 (plain fp32 FMA) or SC_F16 / SC_BF16 (MFMA, fp32 accumulation)
  *   dtype_out   SC_F32 or the same as dtype_in (one round-to-nearest-even at the end)
- *   channels    SC_F32: any C_in, C_out >= 1.  SC_F16 / SC_BF16: C_in a multiple of 32 and
- *               C_out a multiple of 16, both <= 256.
+ *   channels    SC_F32: any C_in >= 1, 1 <= C_out <= 256.  SC_F16 / SC_BF16: C_in one of 32, 64,
+ *               128, 256 and C_out a multiple of 16, 16 <= C_out <= 256.
  *   d_workspace workspace_bytes >= sc_conv_workspace_bytes(...); contents undefined afterwards */
 int sc_conv_fwd(const void* d_feat_in, int64_t n_in,
                 const void* d_weight,
@@ -175,6 +175,23 @@ int sc_hash_lookup(const void* d_table, int64_t n_table,
                    const int32_t* d_query, int64_t n_query, int32_t* d_rows, void* stream);
 
 const char* sc_strerror(int status);
+
+/* ---- measurement aid (not part of the paper's method) -------------------------------------- */
+
+/* Per-kernel timing for benchmarks.  sc_profile_enable(1) clears earlier samples and makes every
+ * later call of this library record a pair of HIP events around each kernel it launches, on the
+ * launch's own stream; sc_profile_enable(0) stops that.  sc_profile_read synchronises the device
+ * and fills up to max_entries entries (one per kernel that ran: name, number of launches, summed
+ * duration in ms); it returns the number of entries written or a negative SC_E* code.  `name`
+ * points to a static string.  This is process-wide state for single-threaded measurement code;
+ * it is off by default and the timed events add a little latency between kernels while on. */
+typedef struct sc_profile_entry {
+    const char* name;
+    int64_t launches;
+    double total_ms;
+} sc_profile_entry;
+int sc_profile_enable(int enable);
+int sc_profile_read(sc_profile_entry* h_entries, int max_entries);
 
 #ifdef __cplusplus
 }

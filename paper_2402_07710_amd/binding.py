@@ -26,7 +26,7 @@ TORCH_DTYPES = {SC_F32: torch.float32, SC_F16: torch.float16, SC_BF16: torch.bfl
 # every symbol include/sc.h declares
 SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_conv_workspace_bytes", "sc_conv_fwd",
-           "sc_counts_read", "sc_kmap_export", "sc_strerror"]
+           "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read"]
 
 
 class ScCounts(ctypes.Structure):
@@ -35,6 +35,10 @@ class ScCounts(ctypes.Structure):
 
 
 COUNTS_BYTES = ctypes.sizeof(ScCounts)
+
+
+class ScProfileEntry(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double)]
 
 
 class ScError(RuntimeError):
@@ -71,6 +75,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_counts_read": (i32, [vp, ctypes.POINTER(ScCounts), vp, i64, i32, i32, i32, vp]),
         "sc_kmap_export": (i32, [vp, i64, i32, i32, i32, ctypes.POINTER(ScCounts), vp, vp, vp, vp]),
         "sc_strerror": (ctypes.c_char_p, [i32]),
+        "sc_profile_enable": (i32, [i32]),
+        "sc_profile_read": (i32, [ctypes.POINTER(ScProfileEntry), i32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -178,6 +184,19 @@ def sc_kmap_export(kmap, n, K, stride, mode, h_counts: ScCounts, stream=None):
     return pin[:P], pout[:P], ost
 
 
+def sc_profile_enable(enable: bool):
+    _check(load().sc_profile_enable(1 if enable else 0), "sc_profile_enable")
+
+
+def sc_profile_read() -> dict:
+    """{kernel name: (launches, total ms)} for the kernels that ran since sc_profile_enable(True)."""
+    arr = (ScProfileEntry * 32)()
+    n = load().sc_profile_read(arr, 32)
+    if n < 0:
+        raise ScError(n, "sc_profile_read")
+    return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].total_ms)) for i in range(n)}
+
+
 # ---- buffers for one layer -------------------------------------------------------------------
 class LayerBuffers:
     """All device buffers one layer needs, allocated once (torch tensors), plus the three calls
@@ -198,15 +217,20 @@ class LayerBuffers:
         self.scratch = torch.empty(max(sc_kmap_scratch_bytes(n, K, stride, mode), 16), **u8)
         self.workspace = torch.empty(max(sc_conv_workspace_bytes(K, C_in, C_out, dtype), 16), **u8)
         self.counts = torch.zeros(COUNTS_BYTES + 8, **u8)
-        self.out_coords = torch.empty((max(self.bound, 1), 4), dtype=torch.int32, device=device)
+        # submanifold outputs are the inputs themselves: no copy is asked for
+        self.out_coords = (None if self.mode == SC_SUBM else
+                           torch.empty((max(self.bound, 1), 4), dtype=torch.int32, device=device))
         self.feat_out = torch.empty((max(self.bound, 1), C_out), dtype=self.out_dtype, device=device)
 
     def hash_build(self, coords, stream=None):
         sc_hash_build(coords, self.table, self.counts, stream)
 
     def kmap_build(self, coords, stream=None):
-        sc_kmap_build(coords, self.table, self.K, self.stride, self.mode, self.out_coords, self.kmap,
+        sc_kmap_build(coords, self.table, self.K, self.stride, self.mode,
+                      None if self.mode == SC_SUBM else self.out_coords, self.kmap,
                       self.scratch, self.counts, stream)
+        if self.mode == SC_SUBM:
+            self.out_coords = coords
 
     def conv_fwd(self, feat_in, weight, stream=None):
         sc_conv_fwd(feat_in, weight, self.feat_out, self.kmap, self.counts, self.K, self.stride, self.mode,

@@ -191,7 +191,7 @@ static int launch_mfma(int KS, dim3 grid, size_t lds, hipStream_t s, const uint1
         if (lds > 48 * 1024 &&                                                                                      \
             hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
             return SC_EHIP;                                                                                         \
-        hipLaunchKernelGGL(fn, grid, dim3(64), lds, s, feat, wp, out, out_f32, start, entries, sstride, K3, C_out,  \
+        SC_LAUNCH(KID_CONV_MFMA, fn, grid, dim3(64), lds, s, feat, wp, out, out_f32, start, entries, sstride, K3, C_out,  \
                            counts, n_out_cap);                                                                      \
         break;                                                                                                      \
     }
@@ -203,7 +203,6 @@ static int launch_mfma(int KS, dim3 grid, size_t lds, hipStream_t s, const uint1
         default: return SC_EINVAL;
     }
 #undef SC_LAUNCH_KS
-    SC_HIP_CHECK_LAUNCH();
     return SC_OK;
 }
 
@@ -250,10 +249,9 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
         if (lds > 48 * 1024 && hipFuncSetAttribute((const void*)k_conv_f32, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                    (int)lds) != hipSuccess)
             return SC_EHIP;
-        hipLaunchKernelGGL(k_conv_f32, dim3((unsigned)tiles), dim3(64), lds, s, (const float*)d_feat_in,
+        SC_LAUNCH(KID_CONV_F32, k_conv_f32, dim3((unsigned)tiles), dim3(64), lds, s, (const float*)d_feat_in,
                            (const float*)d_weight, (float*)d_feat_out, start, entries, L.sstride, L.K3, C_in, C_out,
                            d_counts, n_out_cap);
-        SC_HIP_CHECK_LAUNCH();
         return SC_OK;
     }
 
@@ -261,9 +259,8 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
     const size_t need = sc_conv_workspace_bytes(K, C_in, C_out, dtype_in);
     if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
     const int64_t pack_threads = (int64_t)L.K3 * (C_out / 16) * (C_in / 32) * 64;
-    hipLaunchKernelGGL(k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
+    SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
                        (const uint16_t*)d_weight, (uint4*)d_workspace, L.K3, C_in, C_out);
-    SC_HIP_CHECK_LAUNCH();
     const size_t lds = (size_t)TILE * (C_out + LDS_PAD) * sizeof(float);
     const int out_f32 = dtype_out == SC_F32;
     if (dtype_in == SC_F16)

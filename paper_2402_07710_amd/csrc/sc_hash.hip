@@ -75,8 +75,8 @@ int launch_table_fill(uint64_t* keys, int32_t* vals, uint64_t cap, int fill_vals
                       sc_counts* counts, int64_t n_in, hipStream_t s) {
     unsigned blocks = (unsigned)((cap / 2 + 255) / 256);
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_table_fill, dim3(blocks), dim3(256), 0, s, keys, vals, cap, fill_vals, val_init, counts, n_in);
-    SC_HIP_CHECK_LAUNCH();
+    SC_LAUNCH(KID_TABLE_FILL, k_table_fill, dim3(blocks), dim3(256), 0, s, keys, vals, cap, fill_vals, val_init, counts,
+              n_in);
     return SC_OK;
 }
 
@@ -100,9 +100,8 @@ extern "C" int sc_hash_build(const int32_t* d_coords, int64_t n, void* d_table, 
     const uint64_t cap = (uint64_t)t.mask + 1;
     if (int rc = launch_table_fill(t.keys, t.vals, cap, 0, 0, d_counts, n, s)) return rc;
     if (n > 0) {
-        hipLaunchKernelGGL(k_hash_insert, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                           (const int4*)d_coords, n, t.keys, t.vals, t.mask, d_counts);
-        SC_HIP_CHECK_LAUNCH();
+        SC_LAUNCH(KID_HASH_INSERT, k_hash_insert, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                  (const int4*)d_coords, n, t.keys, t.vals, t.mask, d_counts);
     }
     return SC_OK;
 }
@@ -113,9 +112,9 @@ extern "C" int sc_hash_lookup(const void* d_table, int64_t n_table, const int32_
     if (n_query == 0) return SC_OK;
     if (d_query == nullptr || d_rows == nullptr || !aligned16(d_query) || !aligned16(d_table)) return SC_EINVAL;
     HashTable t = table_view(const_cast<void*>(d_table), n_table);
-    hipLaunchKernelGGL(k_hash_lookup, dim3((unsigned)((n_query + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, (const int4*)d_query, n_query, d_rows);
-    SC_HIP_CHECK_LAUNCH();
+    hipStream_t s = (hipStream_t)stream;
+    SC_LAUNCH(KID_HASH_LOOKUP, k_hash_lookup, dim3((unsigned)((n_query + 255) / 256)), dim3(256), 0, s,
+              (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, (const int4*)d_query, n_query, d_rows);
     return SC_OK;
 }
 

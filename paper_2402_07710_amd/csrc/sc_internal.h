@@ -121,4 +121,22 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
         if (hipGetLastError() != hipSuccess) return SC_EHIP; \
     } while (0)
 
+// ---- optional per-kernel timing (sc_profile_enable / sc_profile_read) --------------------------
+enum KernelId {
+    KID_TABLE_FILL = 0, KID_HASH_INSERT, KID_HASH_LOOKUP, KID_KMAP_HEADER, KID_KMAP_SUBM, KID_FILL_I32,
+    KID_STRIDED_INSERT, KID_STRIDED_FLAGS, KID_SCAN_BLOCKS, KID_STRIDED_PAIRS, KID_KMAP_FROM_OFT,
+    KID_COUNT_PAIRS, KID_EXPORT, KID_WEIGHT_PACK, KID_CONV_MFMA, KID_CONV_F32, KID_MISC, KID_COUNT
+};
+extern bool g_profile_on;
+void profile_mark(int kernel_id, hipStream_t s, bool after);
+
+// Launch a kernel; when profiling is on, bracket it with a pair of HIP events on the same stream.
+#define SC_LAUNCH(kid, kernel, grid, block, lds, stream, ...)                    \
+    do {                                                                         \
+        if (sc::g_profile_on) sc::profile_mark(kid, stream, false);              \
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);       \
+        if (sc::g_profile_on) sc::profile_mark(kid, stream, true);               \
+        if (hipGetLastError() != hipSuccess) return SC_EHIP;                     \
+    } while (0)
+
 }  // namespace sc

@@ -39,7 +39,7 @@ template <int KT>   // KT = 3: unrolled; KT = 0: any odd K at run time
 __global__ void __launch_bounds__(64)
 k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint64_t* __restrict__ keys,
             const int32_t* __restrict__ vals, uint32_t mask, int Krt, uint16_t* __restrict__ start,
-            uint32_t* __restrict__ entries, int sstride, sc_counts* counts) {
+            uint32_t* __restrict__ entries, int sstride, sc_counts* counts, KmapHeader* hdr, KmapHeader hdr_value) {
     const int K = KT ? KT : Krt;
     const int K3 = K * K * K;
     const int pad = (K - 1) / 2;
@@ -51,7 +51,10 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint64_t* __restri
     if (valid) c = coords[row];
     uint16_t* st = start + tile * sstride;
     uint32_t* en = entries + tile * (int64_t)(TILE * K3);
-    if (tile == 0 && lane == 0) counts->n_out = n;
+    if (tile == 0 && lane == 0) {
+        counts->n_out = n;
+        *hdr = hdr_value;
+    }
 
     uint32_t base = 0;
     int k = 0;
@@ -233,11 +236,13 @@ k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
 // Dense offset table -> tile-major lists.  One wavefront per output tile.
 __global__ void __launch_bounds__(64)
 k_kmap_from_oft(const int32_t* __restrict__ oft, int K3, const sc_counts* __restrict__ counts,
-                uint16_t* __restrict__ start, uint32_t* __restrict__ entries, int sstride) {
+                uint16_t* __restrict__ start, uint32_t* __restrict__ entries, int sstride, KmapHeader* hdr,
+                KmapHeader hdr_value) {
     const int lane = threadIdx.x;
     const int64_t tile = blockIdx.x;
     const int64_t row = tile * TILE + lane;
     const bool valid = row < counts->n_out;
+    if (tile == 0 && lane == 0) *hdr = hdr_value;
     uint16_t* st = start + tile * sstride;
     uint32_t* en = entries + tile * (int64_t)(TILE * K3);
     uint32_t base = 0;
@@ -379,25 +384,22 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     KmapHeader h{};
     h.magic = KMAP_MAGIC; h.K = K; h.stride = stride; h.mode = mode;
     h.n_in = n; h.n_out_bound = bound; h.tiles = L.tiles; h.sstride = L.sstride;
-    hipLaunchKernelGGL(k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap, h);
-    SC_HIP_CHECK_LAUNCH();
+    if (n == 0) {
+        SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap, h);
+        SC_LAUNCH(KID_MISC, k_set_n_out, dim3(1), dim3(64), 0, s, d_counts, (int64_t)0);
+        return SC_OK;
+    }
 
     if (mode == SC_SUBM) {
         HashTable t = table_view(const_cast<void*>(d_table), n);
-        if (n == 0) {
-            hipLaunchKernelGGL(k_set_n_out, dim3(1), dim3(64), 0, s, d_counts, (int64_t)0);
-            SC_HIP_CHECK_LAUNCH();
-            return SC_OK;
-        }
         if (K == 3)
-            hipLaunchKernelGGL(k_kmap_subm<3>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
+            SC_LAUNCH(KID_KMAP_SUBM, k_kmap_subm<3>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
                                (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, K, start, entries,
-                               L.sstride, d_counts);
+                               L.sstride, d_counts, (KmapHeader*)d_kmap, h);
         else
-            hipLaunchKernelGGL(k_kmap_subm<0>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
+            SC_LAUNCH(KID_KMAP_SUBM, k_kmap_subm<0>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
                                (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, K, start, entries,
-                               L.sstride, d_counts);
-        SC_HIP_CHECK_LAUNCH();
+                               L.sstride, d_counts, (KmapHeader*)d_kmap, h);
         if (d_out_coords != nullptr && d_out_coords != d_coords) {
             if (hipMemcpyAsync(d_out_coords, d_coords, (size_t)n * 16, hipMemcpyDeviceToDevice, s) != hipSuccess)
                 return SC_EHIP;
@@ -413,32 +415,26 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     if (oft_count > 0) {
         unsigned ob = (unsigned)((oft_count / 4 + 255) / 256);
         if (ob > 4096) ob = 4096;
-        hipLaunchKernelGGL(k_fill_i32, dim3(ob), dim3(256), 0, s, sc_.oft, oft_count, -1);
-        SC_HIP_CHECK_LAUNCH();
+        SC_LAUNCH(KID_FILL_I32, k_fill_i32, dim3(ob), dim3(256), 0, s, sc_.oft, oft_count, -1);
     }
     const int64_t nblk = (n + 1023) / 1024;
     if (n > 0) {
         const unsigned gb = (unsigned)((n + 255) / 256);
-        hipLaunchKernelGGL(k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, sc_.okeys,
+        SC_LAUNCH(KID_STRIDED_INSERT, k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, sc_.okeys,
                            sc_.ovals, sc_.omask, sc_.slot_of, d_counts);
-        SC_HIP_CHECK_LAUNCH();
-        hipLaunchKernelGGL(k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n, (const int32_t*)sc_.slot_of,
+        SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n, (const int32_t*)sc_.slot_of,
                            (const int32_t*)sc_.ovals, sc_.flagword, sc_.word_prefix, sc_.block_sum);
-        SC_HIP_CHECK_LAUNCH();
     }
-    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum, sc_.block_prefix, nblk,
+    SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum, sc_.block_prefix, nblk,
                        d_counts);
-    SC_HIP_CHECK_LAUNCH();
     if (n > 0) {
         const unsigned gb = (unsigned)((n + 255) / 256);
-        hipLaunchKernelGGL(k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
+        SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
                            (const int32_t*)sc_.slot_of, (const int32_t*)sc_.ovals, (const uint64_t*)sc_.flagword,
                            (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, sc_.oft,
                            (int4*)d_out_coords, d_counts);
-        SC_HIP_CHECK_LAUNCH();
-        hipLaunchKernelGGL(k_kmap_from_oft, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int32_t*)sc_.oft, L.K3,
-                           (const sc_counts*)d_counts, start, entries, L.sstride);
-        SC_HIP_CHECK_LAUNCH();
+        SC_LAUNCH(KID_KMAP_FROM_OFT, k_kmap_from_oft, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int32_t*)sc_.oft, L.K3,
+                           (const sc_counts*)d_counts, start, entries, L.sstride, (KmapHeader*)d_kmap, h);
     }
     return SC_OK;
 }
@@ -451,14 +447,12 @@ extern "C" int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts, const vo
         if (!kmap_args_ok(n, K, stride, mode)) return SC_EINVAL;
         const KmapLayout L = kmap_layout(sc_out_bound(n, K, stride, mode), K);
         const uint16_t* start = (const uint16_t*)((const char*)d_kmap + L.off_start);
-        hipLaunchKernelGGL(k_counts_clear_pairs, dim3(1), dim3(256), 0, s, d_counts);
-        SC_HIP_CHECK_LAUNCH();
+        SC_LAUNCH(KID_MISC, k_counts_clear_pairs, dim3(1), dim3(256), 0, s, d_counts);
         if (L.tiles > 0) {
             int64_t items = L.tiles * L.K3;
             unsigned gb = (unsigned)((items + 255) / 256);
             if (gb > 1024) gb = 1024;
-            hipLaunchKernelGGL(k_count_pairs, dim3(gb), dim3(256), 0, s, start, L.sstride, L.K3, L.tiles, d_counts);
-            SC_HIP_CHECK_LAUNCH();
+            SC_LAUNCH(KID_COUNT_PAIRS, k_count_pairs, dim3(gb), dim3(256), 0, s, start, L.sstride, L.K3, L.tiles, d_counts);
         }
     }
     if (hipMemcpyAsync(h_counts, d_counts, sizeof(sc_counts), hipMemcpyDeviceToHost, s) != hipSuccess) return SC_EHIP;
@@ -482,15 +476,13 @@ extern "C" int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, 
     }
     h_start.v[L.K3] = acc;
     if ((int64_t)acc != h_counts->n_pairs) return SC_EINVAL;
-    hipLaunchKernelGGL(k_write_starts, dim3(1), dim3(256), 0, s, h_start, L.K3 + 1, d_offset_start);
-    SC_HIP_CHECK_LAUNCH();
+    SC_LAUNCH(KID_MISC, k_write_starts, dim3(1), dim3(256), 0, s, h_start, L.K3 + 1, d_offset_start);
     const int64_t tiles = (h_counts->n_out + TILE - 1) / TILE;
     if (tiles > 0 && acc > 0) {
-        hipLaunchKernelGGL(k_export, dim3((unsigned)L.K3), dim3(256), 0, s,
+        SC_LAUNCH(KID_EXPORT, k_export, dim3((unsigned)L.K3), dim3(256), 0, s,
                            (const uint16_t*)((const char*)d_kmap + L.off_start),
                            (const uint32_t*)((const char*)d_kmap + L.off_entries), L.sstride, L.K3, tiles,
                            (const int32_t*)d_offset_start, d_pairs_in, d_pairs_out);
-        SC_HIP_CHECK_LAUNCH();
     }
     return SC_OK;
 }
