@@ -34,7 +34,7 @@ def algorithmic_bytes(kernel: str, st: dict) -> float | None:
     N, N_out, P, K3, cap = st["N"], st["N_out"], st["P"], st["K3"], st["cap"]
     C_in, C_out, e = st["C_in"], st["C_out"], st["elem_bytes"]
     if kernel == "k_table_fill":
-        return 8.0 * cap
+        return 16.0 * cap
     if kernel == "k_hash_insert":
         return N * (16 + 8 + 8 + 4)                       # coords, CAS read+write, value
     if kernel == "k_kmap_subm":
@@ -137,7 +137,7 @@ def main() -> int:
     dominant = max(per_step_us, key=per_step_us.get)
     launches_per_step = prof[dominant][0] / args.steps
     avg_s = prof[dominant][1] * 1e-3 / prof[dominant][0]
-    st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=sc.sc_hash_bytes(N) // 12, C_in=C_in, C_out=C_out,
+    st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=sc.sc_hash_bytes(N) // 16, C_in=C_in, C_out=C_out,
               elem_bytes=d_feat.element_size())
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")

@@ -3,23 +3,17 @@
 // The paper scatters the row index into a dense X*Y*Z array (or a hash table for large
 // domains) with one thread per point.  Here the table is an open-addressing hash table in HBM,
 // keyed on the packed 64-bit (b,x,y,z) and claimed with one 64-bit compare-and-swap per point:
-// a 1408x1600x41 LiDAR grid would need 369 MB as a dense int array against ~1.5 MB of table.
+// a 1408x1600x41 LiDAR grid would need 369 MB as a dense int array against ~2 MB of table.
 #include "sc_internal.h"
 
 namespace sc {
 
-// keys <- EMPTY (16-byte stores); optionally vals <- val_init; block 0 resets the counts block.
+// every slot <- {EMPTY, val_init}; block 0 also resets the counts block.
 __global__ void __launch_bounds__(256)
-k_table_fill(uint64_t* __restrict__ keys, int32_t* __restrict__ vals, uint64_t cap, int fill_vals,
-             int32_t val_init, sc_counts* counts, int64_t n_in) {
-    const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+k_table_fill(uint4* __restrict__ slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in) {
     const uint64_t nthr = (uint64_t)gridDim.x * blockDim.x;
-    ulonglong2* k2 = reinterpret_cast<ulonglong2*>(keys);
-    for (uint64_t i = tid; i < cap / 2; i += nthr) k2[i] = make_ulonglong2(KEY_EMPTY, KEY_EMPTY);
-    if (fill_vals) {
-        int4* v4 = reinterpret_cast<int4*>(vals);
-        for (uint64_t i = tid; i < cap / 4; i += nthr) v4[i] = make_int4(val_init, val_init, val_init, val_init);
-    }
+    const uint4 empty = make_uint4(0xffffffffu, 0xffffffffu, (uint32_t)val_init, 0u);
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cap; i += nthr) slots[i] = empty;
     if (counts != nullptr && blockIdx.x == 0) {
         int32_t* w = reinterpret_cast<int32_t*>(counts);
         for (int i = threadIdx.x; i < (int)(sizeof(sc_counts) / 4); i += blockDim.x) w[i] = 0;
@@ -30,8 +24,7 @@ k_table_fill(uint64_t* __restrict__ keys, int32_t* __restrict__ vals, uint64_t c
 
 // One thread per point: claim the first free slot from the key's home slot on.
 __global__ void __launch_bounds__(256)
-k_hash_insert(const int4* __restrict__ coords, int64_t n, uint64_t* keys, int32_t* __restrict__ vals,
-              uint32_t mask, sc_counts* counts) {
+k_hash_insert(const int4* __restrict__ coords, int64_t n, uint4* slots, uint32_t mask, sc_counts* counts) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int4 c = coords[i];
@@ -40,43 +33,37 @@ k_hash_insert(const int4* __restrict__ coords, int64_t n, uint64_t* keys, int32_
         return;
     }
     const uint64_t key = pack_key(c.x, c.y, c.z, c.w);
-    uint32_t slot = home_slot(key, mask);
-    for (uint32_t step = 0; step <= mask; ++step) {
-        uint64_t cur = __hip_atomic_load(&keys[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t t = 0; t <= mask + REHASH_MAX; ++t) {
+        const uint32_t slot = probe_slot(key, t, mask);
+        const uint64_t cur = atomicCAS(reinterpret_cast<unsigned long long*>(&slots[slot]),
+                                       (unsigned long long)KEY_EMPTY, (unsigned long long)key);
         if (cur == KEY_EMPTY) {
-            cur = atomicCAS((unsigned long long*)&keys[slot], (unsigned long long)KEY_EMPTY,
-                            (unsigned long long)key);
-            if (cur == KEY_EMPTY) {
-                vals[slot] = (int32_t)i;
-                return;
-            }
+            reinterpret_cast<int32_t*>(&slots[slot])[2] = (int32_t)i;
+            return;
         }
         if (cur == key) {
             latch_status(counts, SC_EDUP);
             return;
         }
-        slot = (slot + 1) & mask;
     }
     latch_status(counts, SC_EFULL);
 }
 
 __global__ void __launch_bounds__(256)
-k_hash_lookup(const uint64_t* __restrict__ keys, const int32_t* __restrict__ vals, uint32_t mask,
-              const int4* __restrict__ query, int64_t nq, int32_t* __restrict__ rows) {
+k_hash_lookup(const uint4* __restrict__ slots, uint32_t mask, const int4* __restrict__ query, int64_t nq,
+              int32_t* __restrict__ rows) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= nq) return;
     const int4 c = query[i];
     int32_t r = -1;
-    if (in_domain4(c.x, c.y, c.z, c.w)) r = table_find(keys, vals, mask, pack_key(c.x, c.y, c.z, c.w));
+    if (in_domain4(c.x, c.y, c.z, c.w)) r = table_find(slots, mask, pack_key(c.x, c.y, c.z, c.w));
     rows[i] = r;
 }
 
-int launch_table_fill(uint64_t* keys, int32_t* vals, uint64_t cap, int fill_vals, int32_t val_init,
-                      sc_counts* counts, int64_t n_in, hipStream_t s) {
-    unsigned blocks = (unsigned)((cap / 2 + 255) / 256);
+int launch_table_fill(uint4* slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in, hipStream_t s) {
+    unsigned blocks = (unsigned)((cap + 255) / 256);
     if (blocks > 2048) blocks = 2048;
-    SC_LAUNCH(KID_TABLE_FILL, k_table_fill, dim3(blocks), dim3(256), 0, s, keys, vals, cap, fill_vals, val_init, counts,
-              n_in);
+    SC_LAUNCH(KID_TABLE_FILL, k_table_fill, dim3(blocks), dim3(256), 0, s, slots, cap, val_init, counts, n_in);
     return SC_OK;
 }
 
@@ -86,7 +73,7 @@ using namespace sc;
 
 extern "C" size_t sc_hash_bytes(int64_t n) {
     if (n < 0 || n > SC_N_MAX) return 0;
-    return (size_t)hash_capacity(n) * (sizeof(uint64_t) + sizeof(int32_t));
+    return (size_t)hash_capacity(n) * sizeof(uint4);
 }
 
 extern "C" int sc_hash_build(const int32_t* d_coords, int64_t n, void* d_table, size_t table_bytes,
@@ -97,12 +84,10 @@ extern "C" int sc_hash_build(const int32_t* d_coords, int64_t n, void* d_table, 
     if (table_bytes < sc_hash_bytes(n)) return SC_ECAP;
     hipStream_t s = (hipStream_t)stream;
     HashTable t = table_view(d_table, n);
-    const uint64_t cap = (uint64_t)t.mask + 1;
-    if (int rc = launch_table_fill(t.keys, t.vals, cap, 0, 0, d_counts, n, s)) return rc;
-    if (n > 0) {
+    if (int rc = launch_table_fill(t.slots, (uint64_t)t.mask + 1, 0, d_counts, n, s)) return rc;
+    if (n > 0)
         SC_LAUNCH(KID_HASH_INSERT, k_hash_insert, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
-                  (const int4*)d_coords, n, t.keys, t.vals, t.mask, d_counts);
-    }
+                  (const int4*)d_coords, n, t.slots, t.mask, d_counts);
     return SC_OK;
 }
 
@@ -114,7 +99,7 @@ extern "C" int sc_hash_lookup(const void* d_table, int64_t n_table, const int32_
     HashTable t = table_view(const_cast<void*>(d_table), n_table);
     hipStream_t s = (hipStream_t)stream;
     SC_LAUNCH(KID_HASH_LOOKUP, k_hash_lookup, dim3((unsigned)((n_query + 255) / 256)), dim3(256), 0, s,
-              (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, (const int4*)d_query, n_query, d_rows);
+              (const uint4*)t.slots, t.mask, (const int4*)d_query, n_query, d_rows);
     return SC_OK;
 }
 

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "sc.h"
 
@@ -29,49 +30,58 @@ __host__ __device__ inline bool in_domain4(int b, int x, int y, int z) {
     return in_domain(b) && in_domain(x) && in_domain(y) && in_domain(z);
 }
 
-// Home slot of a key.  Keys that differ only in the low bits of z share one hash of the
-// remaining bits and sit side by side, so the z-neighbours a kernel-map probe asks for fall
-// into the same or the adjacent 32-byte sector of the key array.
-constexpr int HASH_RUN_LOG2 = 2;
-__host__ __device__ inline uint32_t home_slot(uint64_t key, uint32_t mask) {
-    uint64_t g = key >> HASH_RUN_LOG2;
-    g *= 0x9E3779B97F4A7C15ull;
-    g ^= g >> 29;
-    g *= 0xBF58476D1CE4E5B9ull;
-    g ^= g >> 32;
-    return (((uint32_t)g << HASH_RUN_LOG2) | ((uint32_t)key & ((1u << HASH_RUN_LOG2) - 1))) & mask;
+// Probe sequence of a key.  The table is cut into regions of 64 slots; a 4x4x4 block of cells
+// owns one region per attempt t (a hash of the block's coordinates and t) and a cell sits at its
+// own place inside the region (its 6 low coordinate bits).  Cells of one block therefore never
+// collide with each other, the 27 neighbours of a voxel fall into at most 8 regions, and voxels
+// that are close in space read the same cache lines of the table.  After REHASH_MAX attempts the
+// sequence continues linearly, so it visits every slot and always ends at an empty one.
+constexpr uint32_t REHASH_MAX = 32;
+__host__ __device__ inline uint32_t mix_block(uint32_t hi, uint32_t lo, uint32_t t) {
+    uint32_t h = hi * 0x85ebca6bu ^ lo * 0xc2b2ae35u ^ (t + 1u) * 0x9e3779b9u;
+    h ^= h >> 15; h *= 0x2c1b3c6du;
+    h ^= h >> 12; h *= 0x297a2d39u;
+    h ^= h >> 15;
+    return h;
+}
+__host__ __device__ inline uint32_t probe_slot(uint64_t key, uint32_t t, uint32_t mask) {
+    const uint32_t hi = (uint32_t)(key >> 32) & 0xfffffffcu;          // b, x >> 2
+    const uint32_t lo = (uint32_t)key & 0xfffcfffcu;                  // y >> 2, z >> 2
+    const uint32_t local = (((uint32_t)(key >> 32) & 3u) << 4) | (((uint32_t)(key >> 16) & 3u) << 2) | ((uint32_t)key & 3u);
+    const uint32_t tt = t < REHASH_MAX ? t : REHASH_MAX - 1;
+    const uint32_t slot = ((mix_block(hi, lo, tt) << 6) | local) + (t - tt);
+    return slot & mask;
 }
 
-// capacity: power of two >= 2n, at least 1024 slots
+// capacity: power of two >= 4n (load factor <= 1/4 keeps probe chains short), at least 1024 slots
 inline uint64_t hash_capacity(int64_t n) {
+    static const int mult = getenv("SC_HASH_MULT") ? atoi(getenv("SC_HASH_MULT")) : 4;
     uint64_t cap = 1024;
-    while (cap < 2ull * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
+    while (cap < (uint64_t)mult * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
     return cap;
 }
 
+// One 16-byte slot per key: {key (8 bytes), value (4), unused (4)}, so a probe is one 16-byte
+// load that brings the key and the row index together.
 struct HashTable {            // view of a caller-owned table buffer
-    uint64_t* keys;           // [cap]
-    int32_t* vals;            // [cap]
+    uint4* slots;             // [cap]: x,y = key (low, high), z = value
     uint32_t mask;            // cap - 1
 };
 inline HashTable table_view(void* p, int64_t n) {
-    uint64_t cap = hash_capacity(n);
     HashTable t;
-    t.keys = (uint64_t*)p;
-    t.vals = (int32_t*)((char*)p + cap * sizeof(uint64_t));
-    t.mask = (uint32_t)(cap - 1);
+    t.slots = (uint4*)p;
+    t.mask = (uint32_t)(hash_capacity(n) - 1);
     return t;
 }
+__host__ __device__ inline uint64_t slot_key(const uint4& s) { return (uint64_t)s.x | ((uint64_t)s.y << 32); }
 
-// Probe for `key`; returns the stored value or -1.  Linear probing, table never full.
-__device__ inline int32_t table_find(const uint64_t* __restrict__ keys, const int32_t* __restrict__ vals,
-                                     uint32_t mask, uint64_t key) {
-    uint32_t slot = home_slot(key, mask);
-    for (uint32_t step = 0; step <= mask; ++step) {
-        uint64_t cur = keys[slot];
-        if (cur == key) return vals[slot];
+// Probe for `key`; returns the stored value or -1.  The table is never full.
+__device__ inline int32_t table_find(const uint4* __restrict__ slots, uint32_t mask, uint64_t key) {
+    for (uint32_t t = 0; t <= mask + REHASH_MAX; ++t) {
+        const uint4 s = slots[probe_slot(key, t, mask)];
+        const uint64_t cur = slot_key(s);
+        if (cur == key) return (int32_t)s.z;
         if (cur == KEY_EMPTY) return -1;
-        slot = (slot + 1) & mask;
     }
     return -1;
 }
@@ -80,9 +90,8 @@ __device__ inline void latch_status(sc_counts* counts, int code) {
     atomicCAS(&counts->status, 0, code);
 }
 
-// keys <- EMPTY, optionally vals <- val_init and *counts reset (defined in sc_hash.hip)
-int launch_table_fill(uint64_t* keys, int32_t* vals, uint64_t cap, int fill_vals, int32_t val_init,
-                      sc_counts* counts, int64_t n_in, hipStream_t s);
+// every slot <- {EMPTY, val_init}; optionally *counts reset (defined in sc_hash.hip)
+int launch_table_fill(uint4* slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in, hipStream_t s);
 
 // ---- kernel-map blob ------------------------------------------------------------------------
 // header | start[T][sstride] (uint16) | entries[T][TILE*K3] (uint32)

@@ -11,6 +11,8 @@
 // a weight matrix into one MFMA tile and sum all offsets of a row on-chip.
 // Strided layers number their output cells in order of first occurrence (min input row per
 // cell + prefix sum), so the result is independent of thread timing, unlike an atomic counter.
+#include <cstdlib>
+
 #include "sc_internal.h"
 
 namespace sc {
@@ -34,57 +36,137 @@ k_set_n_out(sc_counts* counts, int64_t n_out) {
     if (threadIdx.x == 0 && blockIdx.x == 0) counts->n_out = n_out;
 }
 
-// Submanifold: output row = input row.  One wavefront per tile.
-template <int KT>   // KT = 3: unrolled; KT = 0: any odd K at run time
-__global__ void __launch_bounds__(64)
-k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint64_t* __restrict__ keys,
-            const int32_t* __restrict__ vals, uint32_t mask, int Krt, uint16_t* __restrict__ start,
-            uint32_t* __restrict__ entries, int sstride, sc_counts* counts, KmapHeader* hdr, KmapHeader hdr_value) {
-    const int K = KT ? KT : Krt;
-    const int K3 = K * K * K;
-    const int pad = (K - 1) / 2;
-    const int lane = threadIdx.x;
+// Submanifold: output row = input row.  One workgroup of WPT wavefronts per 64-row tile; lane =
+// row, and the K^3 offsets are dealt to the wavefronts CH at a time.  The probes of a row do not
+// depend on each other, so a wavefront issues the loads of its CH offsets together and afterwards
+// re-probes only the offsets whose slot held another key: a tile's K^3 x 64 look-ups cost a few
+// memory round trips instead of K^3.  Each wavefront votes (ballot) on its offsets, the
+// per-offset counts are prefix-summed through LDS, and every lane with a hit writes its pair at
+// (start of its offset) + (hits in lower lanes).
+template <int K, int WPT, int CH>
+__global__ void __launch_bounds__(64 * WPT)
+k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict__ slots, uint32_t mask,
+            uint16_t* __restrict__ start, uint32_t* __restrict__ entries, int sstride, sc_counts* counts,
+            KmapHeader* hdr, KmapHeader hdr_value) {
+    constexpr int K3 = K * K * K, pad = (K - 1) / 2, centre = (K3 - 1) / 2;
+    constexpr int PER_PASS = WPT * CH;
+    constexpr int PASSES = (K3 + PER_PASS - 1) / PER_PASS;
+    constexpr int PER_LANE = (K3 + WAVE - 1) / WAVE;           // offsets per lane in the prefix sum
+    __shared__ int32_t cnt_s[PASSES * PER_PASS];
+    __shared__ int32_t pre_s[PASSES * PER_PASS + 1];
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
     const int64_t row = tile * TILE + lane;
     const bool valid = row < n;
     int4 c = make_int4(0, 0, 0, 0);
     if (valid) c = coords[row];
-    uint16_t* st = start + tile * sstride;
-    uint32_t* en = entries + tile * (int64_t)(TILE * K3);
-    if (tile == 0 && lane == 0) {
+    if (tile == 0 && threadIdx.x == 0) {
         counts->n_out = n;
         *hdr = hdr_value;
     }
 
-    uint32_t base = 0;
-    int k = 0;
-    for (int dx = -pad; dx <= pad; ++dx) {
-        for (int dy = -pad; dy <= pad; ++dy) {
-            for (int dz = -pad; dz <= pad; ++dz, ++k) {
-                int32_t j = -1;
-                if (valid) {
-                    if (dx == 0 && dy == 0 && dz == 0) {
-                        j = (int32_t)row;                       // the centre offset is the identity
-                    } else {
-                        const int x = c.y + dx, y = c.z + dy, z = c.w + dz;
-                        if (in_domain(x) && in_domain(y) && in_domain(z))
-                            j = table_find(keys, vals, mask, pack_key(c.x, x, y, z));
+    auto neighbour_key = [&](int k, bool& inside) -> uint64_t {
+        const int dx = k / (K * K) - pad, dy = (k / K) % K - pad, dz = k % K - pad;
+        const int x = c.y + dx, y = c.z + dy, z = c.w + dz;
+        inside = in_domain(x) && in_domain(y) && in_domain(z);
+        return pack_key(c.x, x, y, z);
+    };
+    auto load_slot = [&](uint32_t slot) -> uint3 { return *reinterpret_cast<const uint3*>(&slots[slot]); };
+
+    int32_t found[PASSES][CH];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int k_base = (p * WPT + w) * CH;
+        uint32_t pending = 0;          // bit u: offset k_base+u still has to be looked up
+        uint3 got[CH];
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int k = k_base + u;
+            bool inside;
+            const uint64_t key = neighbour_key(k, inside);
+            found[p][u] = -1;
+            if (valid && k < K3) {
+                if (k == centre) found[p][u] = (int32_t)row;               // the centre is the row itself
+                else if (inside) pending |= 1u << u;
+            }
+            got[u] = load_slot(probe_slot(key, 0, mask));   // attempt 0 of every offset at once (harmless where nothing is pending)
+        }
+        for (uint32_t t = 0; __any(pending != 0); ++t) {   // ends: every probe sequence reaches an empty slot
+            if (t > 0) {
+#pragma unroll
+                for (int u = 0; u < CH; ++u) {
+                    if (pending & (1u << u)) {
+                        bool inside;
+                        got[u] = load_slot(probe_slot(neighbour_key(k_base + u, inside), t, mask));
                     }
                 }
-                if (lane == 0) st[k] = (uint16_t)base;
-                compact_offset(j >= 0, (uint32_t)j | ((uint32_t)lane << ENTRY_ROW_BITS), en, base);
+            }
+#pragma unroll
+            for (int u = 0; u < CH; ++u) {
+                if (pending & (1u << u)) {
+                    bool inside;
+                    const uint64_t key = neighbour_key(k_base + u, inside);
+                    const uint64_t cur = (uint64_t)got[u].x | ((uint64_t)got[u].y << 32);
+                    if (cur == key) { found[p][u] = (int32_t)got[u].z; pending &= ~(1u << u); }
+                    else if (cur == KEY_EMPTY) pending &= ~(1u << u);
+                }
             }
         }
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const uint64_t vote = __ballot(found[p][u] >= 0);
+            if (lane == 0) cnt_s[k_base + u] = __popcll(vote);
+        }
     }
-    if (lane == 0) st[K3] = (uint16_t)base;
+    __syncthreads();
+    if (w == 0) {          // exclusive prefix over the K^3 counts: PER_LANE per lane, then across lanes
+        int32_t local[PER_LANE];
+        int32_t sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) {
+            const int k = lane * PER_LANE + i;
+            local[i] = k < K3 ? cnt_s[k] : 0;
+            sum += local[i];
+        }
+        int32_t incl = sum;
+#pragma unroll
+        for (int off = 1; off < WAVE; off <<= 1) {
+            const int32_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        int32_t run = incl - sum;
+#pragma unroll
+        for (int i = 0; i < PER_LANE; ++i) {
+            const int k = lane * PER_LANE + i;
+            if (k < K3) pre_s[k] = run;
+            run += local[i];
+        }
+        if (lane == WAVE - 1) pre_s[K3] = incl;
+    }
+    __syncthreads();
+    uint32_t* en = entries + tile * (int64_t)(TILE * K3);
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int k_base = (p * WPT + w) * CH;
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int k = k_base + u;
+            const bool hit = found[p][u] >= 0;
+            const uint64_t vote = __ballot(hit);
+            if (hit && k < K3)
+                en[pre_s[k] + __popcll(vote & lanemask_lt())] = (uint32_t)found[p][u] | ((uint32_t)lane << ENTRY_ROW_BITS);
+        }
+    }
+    uint16_t* st = start + tile * sstride;
+    for (int k = threadIdx.x; k <= K3; k += blockDim.x) st[k] = (uint16_t)pre_s[k];
 }
 
 // ---- strided layers with K == stride ---------------------------------------------------------
 // scratch: output-cell hash (keys, vals = min input row per cell), slot_of[n], flag words,
 // in-block word prefix, block sums / prefixes, and a dense offset table oft[bound][K3].
 struct StridedScratch {
-    uint64_t* okeys;
-    int32_t* ovals;
+    uint4* oslots;           // output-cell table: {key, min input row}
     uint32_t omask;
     int32_t* slot_of;        // [n]
     uint64_t* flagword;      // [ceil(n/64)]  bit i%64 set iff input i is the first of its cell
@@ -101,8 +183,7 @@ inline StridedScratch strided_scratch(void* p, int64_t n, int K) {
     const int K3 = K * K * K;
     size_t off = 0;
     char* b = (char*)p;
-    s.okeys = (uint64_t*)(b + off); off = align_up(off + cap * 8, 256);
-    s.ovals = (int32_t*)(b + off); off = align_up(off + cap * 4, 256);
+    s.oslots = (uint4*)(b + off); off = align_up(off + cap * 16, 256);
     s.omask = (uint32_t)(cap - 1);
     s.slot_of = (int32_t*)(b + off); off = align_up(off + (size_t)n * 4, 256);
     s.flagword = (uint64_t*)(b + off); off = align_up(off + (size_t)words * 8, 256);
@@ -125,8 +206,8 @@ k_fill_i32(int32_t* __restrict__ p, int64_t count, int32_t v) {   // count is a 
 // Each input claims (or finds) the slot of its output cell floor(p/s) (eq. 2, eq. 4) and
 // lowers the slot's value to its own row index.
 __global__ void __launch_bounds__(256)
-k_strided_insert(const int4* __restrict__ coords, int64_t n, int s, uint64_t* okeys, int32_t* ovals,
-                 uint32_t omask, int32_t* __restrict__ slot_of, sc_counts* counts) {
+k_strided_insert(const int4* __restrict__ coords, int64_t n, int s, uint4* oslots, uint32_t omask,
+                 int32_t* __restrict__ slot_of, sc_counts* counts) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int4 c = coords[i];
@@ -135,19 +216,16 @@ k_strided_insert(const int4* __restrict__ coords, int64_t n, int s, uint64_t* ok
         latch_status(counts, SC_ERANGE);
     } else {
         const uint64_t key = pack_key(c.x, c.y / s, c.z / s, c.w / s);
-        uint32_t slot = home_slot(key, omask);
-        for (uint32_t step = 0; step <= omask; ++step) {
-            uint64_t cur = __hip_atomic_load(&okeys[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (cur == KEY_EMPTY)
-                cur = atomicCAS((unsigned long long*)&okeys[slot], (unsigned long long)KEY_EMPTY,
-                                (unsigned long long)key);
+        for (uint32_t t = 0; t <= omask + REHASH_MAX; ++t) {
+            const uint32_t slot = probe_slot(key, t, omask);
+            const uint64_t cur = atomicCAS(reinterpret_cast<unsigned long long*>(&oslots[slot]),
+                                           (unsigned long long)KEY_EMPTY, (unsigned long long)key);
             if (cur == KEY_EMPTY || cur == key) {
                 myslot = (int32_t)slot;
                 break;
             }
-            slot = (slot + 1) & omask;
         }
-        if (myslot >= 0) atomicMin(&ovals[myslot], (int32_t)i);
+        if (myslot >= 0) atomicMin(reinterpret_cast<int32_t*>(&oslots[myslot]) + 2, (int32_t)i);
         else latch_status(counts, SC_EFULL);
     }
     slot_of[i] = myslot;
@@ -156,7 +234,7 @@ k_strided_insert(const int4* __restrict__ coords, int64_t n, int s, uint64_t* ok
 // flag(i) = input i is the first (lowest row) of its cell; one bit per input, plus the
 // exclusive prefix of the flag counts of the 16 words of each 1024-input block.
 __global__ void __launch_bounds__(1024)
-k_strided_flags(int64_t n, const int32_t* __restrict__ slot_of, const int32_t* __restrict__ ovals,
+k_strided_flags(int64_t n, const int32_t* __restrict__ slot_of, const uint4* __restrict__ oslots,
                 uint64_t* __restrict__ flagword, int32_t* __restrict__ word_prefix,
                 int32_t* __restrict__ block_sum) {
     __shared__ int32_t wave_count[16];
@@ -164,7 +242,7 @@ k_strided_flags(int64_t n, const int32_t* __restrict__ slot_of, const int32_t* _
     bool first = false;
     if (i < n) {
         const int32_t sl = slot_of[i];
-        first = sl >= 0 && ovals[sl] == (int32_t)i;
+        first = sl >= 0 && (int32_t)oslots[sl].z == (int32_t)i;
     }
     const uint64_t vote = __ballot(first);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -214,7 +292,7 @@ k_scan_blocks(const int32_t* __restrict__ block_sum, int32_t* __restrict__ block
 // its in-cell offset (eq. 3) and kernel offset (eq. 5), and records itself in the dense table.
 __global__ void __launch_bounds__(256)
 k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
-                const int32_t* __restrict__ slot_of, const int32_t* __restrict__ ovals,
+                const int32_t* __restrict__ slot_of, const uint4* __restrict__ oslots,
                 const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
                 const int32_t* __restrict__ block_prefix, int32_t* oft, int4* __restrict__ out_coords,
                 sc_counts* counts) {
@@ -222,7 +300,7 @@ k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
     if (i >= n) return;
     const int32_t sl = slot_of[i];
     if (sl < 0) return;
-    const int32_t r = ovals[sl];                               // first input of this cell
+    const int32_t r = (int32_t)oslots[sl].z;                   // first input of this cell
     const int32_t o = block_prefix[r >> 10] + word_prefix[r >> 6] +
                       __popcll(flagword[r >> 6] & ((1ull << (r & 63)) - 1ull));
     const int4 c = coords[i];
@@ -392,14 +470,25 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
 
     if (mode == SC_SUBM) {
         HashTable t = table_view(const_cast<void*>(d_table), n);
-        if (K == 3)
-            SC_LAUNCH(KID_KMAP_SUBM, k_kmap_subm<3>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
-                               (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, K, start, entries,
-                               L.sstride, d_counts, (KmapHeader*)d_kmap, h);
-        else
-            SC_LAUNCH(KID_KMAP_SUBM, k_kmap_subm<0>, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int4*)d_coords, n,
-                               (const uint64_t*)t.keys, (const int32_t*)t.vals, t.mask, K, start, entries,
-                               L.sstride, d_counts, (KmapHeader*)d_kmap, h);
+#define SC_SUBM_LAUNCH(KV, WPT, CH)                                                                               \
+    SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH>), dim3((unsigned)L.tiles), dim3(64 * WPT), 0, s,           \
+              (const int4*)d_coords, n, (const uint4*)t.slots, t.mask, start, entries, L.sstride, d_counts,        \
+              (KmapHeader*)d_kmap, h)
+        static const int variant = getenv("SC_KMAP_VARIANT") ? atoi(getenv("SC_KMAP_VARIANT")) : 0;
+        switch (K) {
+            case 1: SC_SUBM_LAUNCH(1, 1, 1); break;
+            case 3:
+                switch (variant) {
+                    case 1: SC_SUBM_LAUNCH(3, 4, 7); break;
+                    case 2: SC_SUBM_LAUNCH(3, 2, 14); break;
+                    default: SC_SUBM_LAUNCH(3, 8, 4); break;
+                }
+                break;
+            case 5: SC_SUBM_LAUNCH(5, 4, 7); break;
+            case 7: SC_SUBM_LAUNCH(7, 4, 7); break;
+            default: return SC_EINVAL;
+        }
+#undef SC_SUBM_LAUNCH
         if (d_out_coords != nullptr && d_out_coords != d_coords) {
             if (hipMemcpyAsync(d_out_coords, d_coords, (size_t)n * 16, hipMemcpyDeviceToDevice, s) != hipSuccess)
                 return SC_EHIP;
@@ -410,7 +499,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     // strided, K == stride
     StridedScratch sc_ = strided_scratch(d_scratch, n, K);
     const uint64_t cap = (uint64_t)sc_.omask + 1;
-    if (int rc = launch_table_fill(sc_.okeys, sc_.ovals, cap, 1, 0x7fffffff, nullptr, 0, s)) return rc;
+    if (int rc = launch_table_fill(sc_.oslots, cap, 0x7fffffff, nullptr, 0, s)) return rc;
     const int64_t oft_count = (int64_t)align_up((size_t)n * L.K3, 4);
     if (oft_count > 0) {
         unsigned ob = (unsigned)((oft_count / 4 + 255) / 256);
@@ -420,17 +509,17 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     const int64_t nblk = (n + 1023) / 1024;
     if (n > 0) {
         const unsigned gb = (unsigned)((n + 255) / 256);
-        SC_LAUNCH(KID_STRIDED_INSERT, k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, sc_.okeys,
-                           sc_.ovals, sc_.omask, sc_.slot_of, d_counts);
+        SC_LAUNCH(KID_STRIDED_INSERT, k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, sc_.oslots,
+                           sc_.omask, sc_.slot_of, d_counts);
         SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n, (const int32_t*)sc_.slot_of,
-                           (const int32_t*)sc_.ovals, sc_.flagword, sc_.word_prefix, sc_.block_sum);
+                           (const uint4*)sc_.oslots, sc_.flagword, sc_.word_prefix, sc_.block_sum);
     }
     SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum, sc_.block_prefix, nblk,
                        d_counts);
     if (n > 0) {
         const unsigned gb = (unsigned)((n + 255) / 256);
         SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
-                           (const int32_t*)sc_.slot_of, (const int32_t*)sc_.ovals, (const uint64_t*)sc_.flagword,
+                           (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
                            (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, sc_.oft,
                            (int4*)d_out_coords, d_counts);
         SC_LAUNCH(KID_KMAP_FROM_OFT, k_kmap_from_oft, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int32_t*)sc_.oft, L.K3,

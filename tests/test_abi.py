@@ -37,10 +37,10 @@ def test_counts_struct_layout():
 
 
 def test_size_queries(lib):
-    assert lib.sc_hash_bytes(0) == 1024 * 12
-    assert lib.sc_hash_bytes(1000) == 2048 * 12
-    assert lib.sc_hash_bytes(1024) == 2048 * 12
-    assert lib.sc_hash_bytes(1025) == 4096 * 12
+    assert lib.sc_hash_bytes(0) == 1024 * 16
+    assert lib.sc_hash_bytes(1000) == 2048 * 16
+    assert lib.sc_hash_bytes(1024) == 2048 * 16
+    assert lib.sc_hash_bytes(1025) == 4096 * 16
     assert lib.sc_hash_bytes(-1) == 0
     assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
     assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
