@@ -12,7 +12,7 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libsc.so")
+LIB_PATH = os.environ.get("SC_LIB_PATH", os.path.join(HERE, "libsc.so"))   # override: development builds
 
 SC_OK, SC_EINVAL, SC_ERANGE, SC_EDUP, SC_ECAP, SC_EHIP, SC_EFULL = 0, -1, -2, -3, -4, -5, -6
 SC_SUBM, SC_STRIDED = 0, 1

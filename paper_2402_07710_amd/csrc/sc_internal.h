@@ -13,8 +13,6 @@ namespace sc {
 constexpr int WAVE = 64;                      // CDNA wavefront
 constexpr int TILE = 64;                      // output rows per kernel-map tile (= one wavefront)
 constexpr uint64_t KEY_EMPTY = ~0ull;         // (65535,65535,65535,65535): outside the domain
-constexpr uint32_t ENTRY_ROW_BITS = 26;       // kernel-map entry = in_row | out_slot << 26
-constexpr uint32_t ENTRY_ROW_MASK = (1u << ENTRY_ROW_BITS) - 1;
 constexpr uint32_t KMAP_MAGIC = 0x70614d6bu;
 
 // ---- coordinate keys ------------------------------------------------------------------------
@@ -94,32 +92,36 @@ __device__ inline void latch_status(sc_counts* counts, int code) {
 int launch_table_fill(uint4* slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in, hipStream_t s);
 
 // ---- kernel-map blob ------------------------------------------------------------------------
-// header | start[T][sstride] (uint16) | entries[T][TILE*K3] (uint32)
-// start[t][k] .. start[t][k+1] delimit tile t's pairs of offset k inside entries[t][...].
+// header | mask[T][4][mw] (uint32) | nbr[T][K3][TILE] (int32)
+// Outputs are cut into tiles of 64 consecutive rows.  nbr[t][k][j] is the input row paired with
+// output row 64t+j at offset k, or -1: the paper's offset table (Section III-C.2), stored
+// offset-major inside a tile so that the 16 rows an MFMA group takes are 64 contiguous bytes.
+// Bit k of mask[t][q] (word k/32) says whether any of the rows 16q..16q+15 of tile t has a
+// neighbour at offset k; the convolution skips the groups whose bit is clear.
 struct KmapHeader {
     uint32_t magic;
     int32_t K, stride, mode;
     int64_t n_in, n_out_bound;
     int64_t tiles;
-    int32_t sstride, reserved;
+    int32_t mw, reserved;
 };
 struct KmapLayout {
     int64_t tiles;        // T = ceil(n_out_bound / TILE)
     int K3;
-    int sstride;          // uint16 per tile in start[], multiple of 32
-    size_t off_start;     // byte offsets inside the blob
-    size_t off_entries;
+    int mw;               // mask words per (tile, quarter) = ceil(K3 / 32)
+    size_t off_mask;      // byte offsets inside the blob
+    size_t off_nbr;
     size_t bytes;
 };
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline KmapLayout kmap_layout(int64_t n_out_bound, int K) {
     KmapLayout L;
     L.K3 = K * K * K;
+    L.mw = (L.K3 + 31) / 32;
     L.tiles = (n_out_bound + TILE - 1) / TILE;
-    L.sstride = (int)align_up((size_t)L.K3 + 1, 32);
-    L.off_start = 256;
-    L.off_entries = align_up(L.off_start + (size_t)L.tiles * L.sstride * sizeof(uint16_t), 256);
-    L.bytes = align_up(L.off_entries + (size_t)L.tiles * TILE * L.K3 * sizeof(uint32_t), 256);
+    L.off_mask = 256;
+    L.off_nbr = align_up(L.off_mask + (size_t)L.tiles * 4 * L.mw * sizeof(uint32_t), 256);
+    L.bytes = align_up(L.off_nbr + (size_t)L.tiles * L.K3 * TILE * sizeof(int32_t), 256);
     return L;
 }
 
@@ -129,6 +131,19 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
     do {                                             \
         if (hipGetLastError() != hipSuccess) return SC_EHIP; \
     } while (0)
+
+// ---- phase marks inside kernels (development builds with -DSC_TRACE only) ----------------------
+// SC_MARK(i) stores the 100 MHz wall clock of the calling wavefront's first lane into
+// trace[workgroup][i]; it compiles to nothing in the product build.
+#ifdef SC_TRACE
+extern __device__ long long* g_trace_buf;
+#define SC_MARK(i)                                                                              \
+    do {                                                                                        \
+        if (g_trace_buf != nullptr && threadIdx.x == 0) g_trace_buf[(size_t)blockIdx.x * 16 + (i)] = wall_clock64(); \
+    } while (0)
+#else
+#define SC_MARK(i) do { } while (0)
+#endif
 
 // ---- optional per-kernel timing (sc_profile_enable / sc_profile_read) --------------------------
 enum KernelId {

@@ -2,15 +2,16 @@
 // eq. 1-5 and Section III-D for strided layers).
 //
 // The paper writes a dense N x K^3 table of neighbour rows (-1 where there is none) with one
-// thread per point, and for strided layers counts the distinct output cells with an atomic
-// exchange on a status table plus an atomic counter.  Here one 64-lane wavefront owns 64
-// consecutive output rows: every lane probes the location table for one row's neighbour at
-// offset k, the wavefront votes (ballot) and each lane with a hit takes the next free place in
-// the tile's list for offset k (prefix count of the vote).  No atomics, no empty entries, and a
-// layout - tile-major, grouped by offset - that lets the convolution kernel pack rows that share
-// a weight matrix into one MFMA tile and sum all offsets of a row on-chip.
-// Strided layers number their output cells in order of first occurrence (min input row per
-// cell + prefix sum), so the result is independent of thread timing, unlike an atomic counter.
+// thread per point probing the location table K^3 times in a loop, and for strided layers counts
+// the distinct output cells with an atomic exchange on a status table plus an atomic counter.
+// Here the table is the same offset table, laid out for the matrix cores: outputs are cut into
+// tiles of 64 rows, a tile stores its K^3 x 64 neighbour rows offset-major, and a bit per
+// (16-row group, offset) records whether the group has any neighbour there, so the convolution
+// only touches groups that exist.  Look-ups are issued many at a time (they are independent), not
+// one after the other.  Strided layers number their output cells in order of first occurrence
+// (min input row per cell + prefix sum), so the result does not depend on thread timing, unlike
+// an atomic counter.  The plain per-offset pair lists are produced on demand (sc_kmap_export) by
+// ballot + prefix-count compaction of the table.
 #include <cstdlib>
 
 #include "sc_internal.h"
@@ -18,13 +19,6 @@
 namespace sc {
 
 __device__ inline uint64_t lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
-
-// Append the lanes that have `found` to the tile's list of the current offset.
-__device__ inline void compact_offset(bool found, uint32_t value, uint32_t* __restrict__ en, uint32_t& base) {
-    const uint64_t vote = __ballot(found);
-    if (found) en[base + (uint32_t)__popcll(vote & lanemask_lt())] = value;
-    base += (uint32_t)__popcll(vote);
-}
 
 __global__ void __launch_bounds__(64)
 k_kmap_header(KmapHeader* hdr, KmapHeader value) {
@@ -40,23 +34,23 @@ k_set_n_out(sc_counts* counts, int64_t n_out) {
 // row, and the K^3 offsets are dealt to the wavefronts CH at a time.  The probes of a row do not
 // depend on each other, so a wavefront issues the loads of its CH offsets together and afterwards
 // re-probes only the offsets whose slot held another key: a tile's K^3 x 64 look-ups cost a few
-// memory round trips instead of K^3.  Each wavefront votes (ballot) on its offsets, the
-// per-offset counts are prefix-summed through LDS, and every lane with a hit writes its pair at
-// (start of its offset) + (hits in lower lanes).
+// memory round trips instead of K^3.  Each wavefront then stores its offsets' 64 results as one
+// 256-byte line of the tile and votes (ballot) on which 16-row groups have a neighbour.
 template <int K, int WPT, int CH>
 __global__ void __launch_bounds__(64 * WPT)
 k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict__ slots, uint32_t mask,
-            uint16_t* __restrict__ start, uint32_t* __restrict__ entries, int sstride, sc_counts* counts,
-            KmapHeader* hdr, KmapHeader hdr_value) {
+            uint32_t* __restrict__ gmask, int32_t* __restrict__ nbr, sc_counts* counts, KmapHeader* hdr,
+            KmapHeader hdr_value) {
     constexpr int K3 = K * K * K, pad = (K - 1) / 2, centre = (K3 - 1) / 2;
     constexpr int PER_PASS = WPT * CH;
     constexpr int PASSES = (K3 + PER_PASS - 1) / PER_PASS;
-    constexpr int PER_LANE = (K3 + WAVE - 1) / WAVE;           // offsets per lane in the prefix sum
-    __shared__ int32_t cnt_s[PASSES * PER_PASS];
-    __shared__ int32_t pre_s[PASSES * PER_PASS + 1];
+    constexpr int MW = (K3 + 31) / 32;
+    __shared__ uint32_t mask_s[4 * MW];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t tile = blockIdx.x;
+    SC_MARK(0);
+    if (threadIdx.x < 4 * MW) mask_s[threadIdx.x] = 0u;
     const int64_t row = tile * TILE + lane;
     const bool valid = row < n;
     int4 c = make_int4(0, 0, 0, 0);
@@ -65,6 +59,7 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
         counts->n_out = n;
         *hdr = hdr_value;
     }
+    __syncthreads();
 
     auto neighbour_key = [&](int k, bool& inside) -> uint64_t {
         const int dx = k / (K * K) - pad, dy = (k / K) % K - pad, dz = k % K - pad;
@@ -74,25 +69,28 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
     };
     auto load_slot = [&](uint32_t slot) -> uint3 { return *reinterpret_cast<const uint3*>(&slots[slot]); };
 
-    int32_t found[PASSES][CH];
+    int32_t* tile_nbr = nbr + tile * (int64_t)(K3 * TILE);
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
         const int k_base = (p * WPT + w) * CH;
         uint32_t pending = 0;          // bit u: offset k_base+u still has to be looked up
+        int32_t found[CH];
         uint3 got[CH];
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int k = k_base + u;
             bool inside;
             const uint64_t key = neighbour_key(k, inside);
-            found[p][u] = -1;
+            found[u] = -1;
             if (valid && k < K3) {
-                if (k == centre) found[p][u] = (int32_t)row;               // the centre is the row itself
+                if (k == centre) found[u] = (int32_t)row;                  // the centre is the row itself
                 else if (inside) pending |= 1u << u;
             }
             got[u] = load_slot(probe_slot(key, 0, mask));   // attempt 0 of every offset at once (harmless where nothing is pending)
         }
+        SC_MARK(1);
         for (uint32_t t = 0; __any(pending != 0); ++t) {   // ends: every probe sequence reaches an empty slot
+            if (t == 1) SC_MARK(2);
             if (t > 0) {
 #pragma unroll
                 for (int u = 0; u < CH; ++u) {
@@ -108,63 +106,31 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
                     bool inside;
                     const uint64_t key = neighbour_key(k_base + u, inside);
                     const uint64_t cur = (uint64_t)got[u].x | ((uint64_t)got[u].y << 32);
-                    if (cur == key) { found[p][u] = (int32_t)got[u].z; pending &= ~(1u << u); }
+                    if (cur == key) { found[u] = (int32_t)got[u].z; pending &= ~(1u << u); }
                     else if (cur == KEY_EMPTY) pending &= ~(1u << u);
                 }
             }
         }
-#pragma unroll
-        for (int u = 0; u < CH; ++u) {
-            const uint64_t vote = __ballot(found[p][u] >= 0);
-            if (lane == 0) cnt_s[k_base + u] = __popcll(vote);
-        }
-    }
-    __syncthreads();
-    if (w == 0) {          // exclusive prefix over the K^3 counts: PER_LANE per lane, then across lanes
-        int32_t local[PER_LANE];
-        int32_t sum = 0;
-#pragma unroll
-        for (int i = 0; i < PER_LANE; ++i) {
-            const int k = lane * PER_LANE + i;
-            local[i] = k < K3 ? cnt_s[k] : 0;
-            sum += local[i];
-        }
-        int32_t incl = sum;
-#pragma unroll
-        for (int off = 1; off < WAVE; off <<= 1) {
-            const int32_t up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-        }
-        int32_t run = incl - sum;
-#pragma unroll
-        for (int i = 0; i < PER_LANE; ++i) {
-            const int k = lane * PER_LANE + i;
-            if (k < K3) pre_s[k] = run;
-            run += local[i];
-        }
-        if (lane == WAVE - 1) pre_s[K3] = incl;
-    }
-    __syncthreads();
-    uint32_t* en = entries + tile * (int64_t)(TILE * K3);
-#pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-        const int k_base = (p * WPT + w) * CH;
+        SC_MARK(3);
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int k = k_base + u;
-            const bool hit = found[p][u] >= 0;
-            const uint64_t vote = __ballot(hit);
-            if (hit && k < K3)
-                en[pre_s[k] + __popcll(vote & lanemask_lt())] = (uint32_t)found[p][u] | ((uint32_t)lane << ENTRY_ROW_BITS);
+            if (k < K3) {
+                tile_nbr[k * TILE + lane] = found[u];
+                const uint64_t vote = __ballot(found[u] >= 0);
+                if (lane < 4 && ((vote >> (16 * lane)) & 0xffffull) != 0) atomicOr(&mask_s[lane * MW + (k >> 5)], 1u << (k & 31));
+            }
         }
     }
-    uint16_t* st = start + tile * sstride;
-    for (int k = threadIdx.x; k <= K3; k += blockDim.x) st[k] = (uint16_t)pre_s[k];
+    __syncthreads();
+    SC_MARK(4);
+    if (threadIdx.x < 4 * MW) gmask[tile * (4 * MW) + threadIdx.x] = mask_s[threadIdx.x];
+    SC_MARK(5);
 }
 
 // ---- strided layers with K == stride ---------------------------------------------------------
-// scratch: output-cell hash (keys, vals = min input row per cell), slot_of[n], flag words,
-// in-block word prefix, block sums / prefixes, and a dense offset table oft[bound][K3].
+// scratch: output-cell table (key -> min input row of the cell), slot_of[n], flag words,
+// in-block word prefix, block sums / prefixes.
 struct StridedScratch {
     uint4* oslots;           // output-cell table: {key, min input row}
     uint32_t omask;
@@ -173,14 +139,12 @@ struct StridedScratch {
     int32_t* word_prefix;    // [ceil(n/64)]  flags before this word inside its 1024-block
     int32_t* block_sum;      // [nblk]
     int32_t* block_prefix;   // [nblk]
-    int32_t* oft;            // [bound][K3]
     size_t bytes;
 };
-inline StridedScratch strided_scratch(void* p, int64_t n, int K) {
+inline StridedScratch strided_scratch(void* p, int64_t n) {
     StridedScratch s;
     const uint64_t cap = hash_capacity(n);
     const int64_t words = (n + 63) / 64, nblk = (n + 1023) / 1024;
-    const int K3 = K * K * K;
     size_t off = 0;
     char* b = (char*)p;
     s.oslots = (uint4*)(b + off); off = align_up(off + cap * 16, 256);
@@ -190,17 +154,20 @@ inline StridedScratch strided_scratch(void* p, int64_t n, int K) {
     s.word_prefix = (int32_t*)(b + off); off = align_up(off + (size_t)words * 4, 256);
     s.block_sum = (int32_t*)(b + off); off = align_up(off + (size_t)nblk * 4, 256);
     s.block_prefix = (int32_t*)(b + off); off = align_up(off + (size_t)nblk * 4, 256);
-    s.oft = (int32_t*)(b + off); off = align_up(off + (size_t)n * K3 * 4, 256);
     s.bytes = off + 256;
     return s;
 }
 
+// One pass that prepares a strided build: output table <- empty, masks <- 0, offset table <- -1.
 __global__ void __launch_bounds__(256)
-k_fill_i32(int32_t* __restrict__ p, int64_t count, int32_t v) {   // count is a multiple of 4
-    int4* p4 = reinterpret_cast<int4*>(p);
+k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, uint4* __restrict__ gmask16, int64_t mask_vec,
+               int4* __restrict__ nbr16, int64_t nbr_vec) {
     const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count / 4; i += nthr)
-        p4[i] = make_int4(v, v, v, v);
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint4 empty = make_uint4(0xffffffffu, 0xffffffffu, 0x7fffffffu, 0u);
+    for (int64_t i = tid; i < (int64_t)cap; i += nthr) oslots[i] = empty;
+    for (int64_t i = tid; i < mask_vec; i += nthr) gmask16[i] = make_uint4(0u, 0u, 0u, 0u);
+    for (int64_t i = tid; i < nbr_vec; i += nthr) nbr16[i] = make_int4(-1, -1, -1, -1);
 }
 
 // Each input claims (or finds) the slot of its output cell floor(p/s) (eq. 2, eq. 4) and
@@ -289,14 +256,15 @@ k_scan_blocks(const int32_t* __restrict__ block_sum, int32_t* __restrict__ block
 }
 
 // Every input finds its output row (rank of its cell's first input among all first inputs),
-// its in-cell offset (eq. 3) and kernel offset (eq. 5), and records itself in the dense table.
+// its in-cell offset (eq. 3) and kernel offset (eq. 5), and records itself in the offset table.
 __global__ void __launch_bounds__(256)
-k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
+k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3, int mw,
                 const int32_t* __restrict__ slot_of, const uint4* __restrict__ oslots,
                 const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
-                const int32_t* __restrict__ block_prefix, int32_t* oft, int4* __restrict__ out_coords,
-                sc_counts* counts) {
+                const int32_t* __restrict__ block_prefix, uint32_t* gmask, int32_t* nbr,
+                int4* __restrict__ out_coords, sc_counts* counts, KmapHeader* hdr, KmapHeader hdr_value) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) *hdr = hdr_value;
     if (i >= n) return;
     const int32_t sl = slot_of[i];
     if (sl < 0) return;
@@ -306,31 +274,12 @@ k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
     const int4 c = coords[i];
     const int qx = c.y / s, qy = c.z / s, qz = c.w / s;
     const int k = ((c.y - qx * s) * s + (c.z - qy * s)) * s + (c.w - qz * s);
-    const int32_t old = atomicExch(&oft[(int64_t)o * K3 + k], (int32_t)i);
+    const int64_t tile = o >> 6;
+    const int j = o & 63;
+    const int32_t old = atomicExch(&nbr[(tile * K3 + k) * TILE + j], (int32_t)i);
     if (old != -1) latch_status(counts, SC_EDUP);
+    atomicOr(&gmask[(tile * 4 + (j >> 4)) * mw + (k >> 5)], 1u << (k & 31));
     if (r == (int32_t)i) out_coords[o] = make_int4(c.x, qx, qy, qz);
-}
-
-// Dense offset table -> tile-major lists.  One wavefront per output tile.
-__global__ void __launch_bounds__(64)
-k_kmap_from_oft(const int32_t* __restrict__ oft, int K3, const sc_counts* __restrict__ counts,
-                uint16_t* __restrict__ start, uint32_t* __restrict__ entries, int sstride, KmapHeader* hdr,
-                KmapHeader hdr_value) {
-    const int lane = threadIdx.x;
-    const int64_t tile = blockIdx.x;
-    const int64_t row = tile * TILE + lane;
-    const bool valid = row < counts->n_out;
-    if (tile == 0 && lane == 0) *hdr = hdr_value;
-    uint16_t* st = start + tile * sstride;
-    uint32_t* en = entries + tile * (int64_t)(TILE * K3);
-    uint32_t base = 0;
-    for (int k = 0; k < K3; ++k) {
-        int32_t j = -1;
-        if (valid) j = oft[row * K3 + k];
-        if (lane == 0) st[k] = (uint16_t)base;
-        compact_offset(j >= 0, (uint32_t)j | ((uint32_t)lane << ENTRY_ROW_BITS), en, base);
-    }
-    if (lane == 0) st[K3] = (uint16_t)base;
 }
 
 // ---- reading a map back -----------------------------------------------------------------------
@@ -340,21 +289,21 @@ k_counts_clear_pairs(sc_counts* counts) {
     if (threadIdx.x == 0) counts->n_pairs = 0;
 }
 
+// One wavefront per (tile, offset) line of the table: count the rows that have a neighbour.
 __global__ void __launch_bounds__(256)
-k_count_pairs(const uint16_t* __restrict__ start, int sstride, int K3, int64_t tiles_bound, sc_counts* counts) {
+k_count_pairs(const int32_t* __restrict__ nbr, int K3, int64_t tiles_bound, sc_counts* counts) {
     __shared__ int32_t hist[343];
     for (int i = threadIdx.x; i < K3; i += blockDim.x) hist[i] = 0;
     __syncthreads();
     int64_t tiles = (counts->n_out + TILE - 1) / TILE;
     if (tiles > tiles_bound) tiles = tiles_bound;
     const int64_t items = tiles * K3;
-    const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; it < items; it += nthr) {
-        const int64_t t = it / K3;
-        const int k = (int)(it - t * K3);
-        const uint16_t* st = start + t * sstride;
-        const int c = (int)st[k + 1] - (int)st[k];
-        if (c) atomicAdd(&hist[k], c);
+    const int lane = threadIdx.x & 63;
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    for (int64_t it = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); it < items; it += nwaves) {
+        const int k = (int)(it % K3);
+        const int c = __popcll(__ballot(nbr[it * TILE + lane] >= 0));
+        if (lane == 0 && c) atomicAdd(&hist[k], c);
     }
     __syncthreads();
     for (int i = threadIdx.x; i < K3; i += blockDim.x) {
@@ -365,43 +314,38 @@ k_count_pairs(const uint16_t* __restrict__ start, int sstride, int K3, int64_t t
     }
 }
 
-// One workgroup per offset k walks the tiles in order and copies each tile's pairs of offset k
-// behind those of the tiles before it: pairs come out ordered by output row.
-__global__ void __launch_bounds__(256)
-k_export(const uint16_t* __restrict__ start, const uint32_t* __restrict__ entries, int sstride, int K3,
-         int64_t tiles, const int32_t* __restrict__ offset_start, int32_t* __restrict__ pairs_in,
-         int32_t* __restrict__ pairs_out) {
-    __shared__ int32_t scan[256];
+// Plain pair lists: one workgroup per offset k walks the tiles in order, 16 tiles (one per
+// wavefront) at a time; the rows with a neighbour are compacted by ballot + prefix count behind
+// those of the earlier tiles, so the pairs of an offset come out ordered by output row.
+__global__ void __launch_bounds__(1024)
+k_export(const int32_t* __restrict__ nbr, int K3, int64_t tiles, const int32_t* __restrict__ offset_start,
+         int32_t* __restrict__ pairs_in, int32_t* __restrict__ pairs_out) {
+    __shared__ int32_t cnt_s[16];
     __shared__ int32_t carry_s;
     const int k = blockIdx.x;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry_s = offset_start[k];
     __syncthreads();
-    for (int64_t base = 0; base < tiles; base += 256) {
-        const int64_t t = base + threadIdx.x;
-        int s0 = 0, cnt = 0;
-        if (t < tiles) {
-            const uint16_t* st = start + t * sstride;
-            s0 = st[k];
-            cnt = (int)st[k + 1] - s0;
-        }
-        scan[threadIdx.x] = cnt;
+    for (int64_t t0 = 0; t0 < tiles; t0 += 16) {
+        const int64_t t = t0 + w;
+        int32_t v = -1;
+        if (t < tiles) v = nbr[(t * K3 + k) * TILE + lane];
+        const uint64_t vote = __ballot(v >= 0);
+        if (lane == 0) cnt_s[w] = __popcll(vote);
         __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {
-            int32_t add = threadIdx.x >= (unsigned)off ? scan[threadIdx.x - off] : 0;
-            __syncthreads();
-            scan[threadIdx.x] += add;
-            __syncthreads();
-        }
-        const int32_t carry = carry_s;
-        int32_t dst = carry + scan[threadIdx.x] - cnt;
-        const uint32_t* en = entries + t * (int64_t)(TILE * K3) + s0;
-        for (int e = 0; e < cnt; ++e) {
-            const uint32_t v = en[e];
-            pairs_in[dst + e] = (int32_t)(v & ENTRY_ROW_MASK);
-            pairs_out[dst + e] = (int32_t)(t * TILE + (v >> ENTRY_ROW_BITS));
+        int32_t base = carry_s;
+        for (int ww = 0; ww < w; ++ww) base += cnt_s[ww];
+        if (v >= 0) {
+            const int32_t dst = base + __popcll(vote & lanemask_lt());
+            pairs_in[dst] = v;
+            pairs_out[dst] = (int32_t)(t * TILE + lane);
         }
         __syncthreads();
-        if (threadIdx.x == 255) carry_s = carry + scan[255];
+        if (threadIdx.x == 0) {
+            int32_t total = 0;
+            for (int ww = 0; ww < 16; ++ww) total += cnt_s[ww];
+            carry_s += total;
+        }
         __syncthreads();
     }
 }
@@ -438,7 +382,7 @@ extern "C" size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode) {
 extern "C" size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode) {
     if (!kmap_args_ok(n, K, stride, mode)) return 0;
     if (mode == SC_SUBM) return 256;
-    return strided_scratch(nullptr, n, K).bytes;
+    return strided_scratch(nullptr, n).bytes;
 }
 
 extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
@@ -457,11 +401,11 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     hipStream_t s = (hipStream_t)stream;
     const int64_t bound = sc_out_bound(n, K, stride, mode);
     const KmapLayout L = kmap_layout(bound, K);
-    uint16_t* start = (uint16_t*)((char*)d_kmap + L.off_start);
-    uint32_t* entries = (uint32_t*)((char*)d_kmap + L.off_entries);
+    uint32_t* gmask = (uint32_t*)((char*)d_kmap + L.off_mask);
+    int32_t* nbr = (int32_t*)((char*)d_kmap + L.off_nbr);
     KmapHeader h{};
     h.magic = KMAP_MAGIC; h.K = K; h.stride = stride; h.mode = mode;
-    h.n_in = n; h.n_out_bound = bound; h.tiles = L.tiles; h.sstride = L.sstride;
+    h.n_in = n; h.n_out_bound = bound; h.tiles = L.tiles; h.mw = L.mw;
     if (n == 0) {
         SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap, h);
         SC_LAUNCH(KID_MISC, k_set_n_out, dim3(1), dim3(64), 0, s, d_counts, (int64_t)0);
@@ -472,20 +416,12 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         HashTable t = table_view(const_cast<void*>(d_table), n);
 #define SC_SUBM_LAUNCH(KV, WPT, CH)                                                                               \
     SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH>), dim3((unsigned)L.tiles), dim3(64 * WPT), 0, s,           \
-              (const int4*)d_coords, n, (const uint4*)t.slots, t.mask, start, entries, L.sstride, d_counts,        \
-              (KmapHeader*)d_kmap, h)
-        static const int variant = getenv("SC_KMAP_VARIANT") ? atoi(getenv("SC_KMAP_VARIANT")) : 0;
+              (const int4*)d_coords, n, (const uint4*)t.slots, t.mask, gmask, nbr, d_counts, (KmapHeader*)d_kmap, h)
         switch (K) {
             case 1: SC_SUBM_LAUNCH(1, 1, 1); break;
-            case 3:
-                switch (variant) {
-                    case 1: SC_SUBM_LAUNCH(3, 4, 7); break;
-                    case 2: SC_SUBM_LAUNCH(3, 2, 14); break;
-                    default: SC_SUBM_LAUNCH(3, 8, 4); break;
-                }
-                break;
-            case 5: SC_SUBM_LAUNCH(5, 4, 7); break;
-            case 7: SC_SUBM_LAUNCH(7, 4, 7); break;
+            case 3: SC_SUBM_LAUNCH(3, 8, 4); break;
+            case 5: SC_SUBM_LAUNCH(5, 8, 4); break;
+            case 7: SC_SUBM_LAUNCH(7, 8, 4); break;
             default: return SC_EINVAL;
         }
 #undef SC_SUBM_LAUNCH
@@ -497,34 +433,29 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     }
 
     // strided, K == stride
-    StridedScratch sc_ = strided_scratch(d_scratch, n, K);
+    StridedScratch sc_ = strided_scratch(d_scratch, n);
     const uint64_t cap = (uint64_t)sc_.omask + 1;
-    if (int rc = launch_table_fill(sc_.oslots, cap, 0x7fffffff, nullptr, 0, s)) return rc;
-    const int64_t oft_count = (int64_t)align_up((size_t)n * L.K3, 4);
-    if (oft_count > 0) {
-        unsigned ob = (unsigned)((oft_count / 4 + 255) / 256);
-        if (ob > 4096) ob = 4096;
-        SC_LAUNCH(KID_FILL_I32, k_fill_i32, dim3(ob), dim3(256), 0, s, sc_.oft, oft_count, -1);
+    const int64_t mask_vec = (int64_t)((L.off_nbr - L.off_mask) / 16);
+    const int64_t nbr_vec = (int64_t)((L.bytes - L.off_nbr) / 16);
+    {
+        int64_t work = (int64_t)cap > nbr_vec ? (int64_t)cap : nbr_vec;
+        unsigned fb = (unsigned)((work + 255) / 256);
+        if (fb > 4096) fb = 4096;
+        SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, sc_.oslots, cap, (uint4*)gmask, mask_vec,
+                  (int4*)nbr, nbr_vec);
     }
     const int64_t nblk = (n + 1023) / 1024;
-    if (n > 0) {
-        const unsigned gb = (unsigned)((n + 255) / 256);
-        SC_LAUNCH(KID_STRIDED_INSERT, k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, sc_.oslots,
-                           sc_.omask, sc_.slot_of, d_counts);
-        SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n, (const int32_t*)sc_.slot_of,
-                           (const uint4*)sc_.oslots, sc_.flagword, sc_.word_prefix, sc_.block_sum);
-    }
-    SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum, sc_.block_prefix, nblk,
-                       d_counts);
-    if (n > 0) {
-        const unsigned gb = (unsigned)((n + 255) / 256);
-        SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
-                           (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
-                           (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, sc_.oft,
-                           (int4*)d_out_coords, d_counts);
-        SC_LAUNCH(KID_KMAP_FROM_OFT, k_kmap_from_oft, dim3((unsigned)L.tiles), dim3(64), 0, s, (const int32_t*)sc_.oft, L.K3,
-                           (const sc_counts*)d_counts, start, entries, L.sstride, (KmapHeader*)d_kmap, h);
-    }
+    const unsigned gb = (unsigned)((n + 255) / 256);
+    SC_LAUNCH(KID_STRIDED_INSERT, k_strided_insert, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride,
+              sc_.oslots, sc_.omask, sc_.slot_of, d_counts);
+    SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n,
+              (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, sc_.flagword, sc_.word_prefix, sc_.block_sum);
+    SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum,
+              sc_.block_prefix, nblk, d_counts);
+    SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
+              L.mw, (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
+              (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, gmask, nbr, (int4*)d_out_coords,
+              d_counts, (KmapHeader*)d_kmap, h);
     return SC_OK;
 }
 
@@ -535,13 +466,13 @@ extern "C" int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts, const vo
     if (d_kmap != nullptr) {
         if (!kmap_args_ok(n, K, stride, mode)) return SC_EINVAL;
         const KmapLayout L = kmap_layout(sc_out_bound(n, K, stride, mode), K);
-        const uint16_t* start = (const uint16_t*)((const char*)d_kmap + L.off_start);
         SC_LAUNCH(KID_MISC, k_counts_clear_pairs, dim3(1), dim3(256), 0, s, d_counts);
         if (L.tiles > 0) {
             int64_t items = L.tiles * L.K3;
-            unsigned gb = (unsigned)((items + 255) / 256);
-            if (gb > 1024) gb = 1024;
-            SC_LAUNCH(KID_COUNT_PAIRS, k_count_pairs, dim3(gb), dim3(256), 0, s, start, L.sstride, L.K3, L.tiles, d_counts);
+            unsigned gb = (unsigned)((items + 3) / 4);
+            if (gb > 2048) gb = 2048;
+            SC_LAUNCH(KID_COUNT_PAIRS, k_count_pairs, dim3(gb), dim3(256), 0, s,
+                      (const int32_t*)((const char*)d_kmap + L.off_nbr), L.K3, L.tiles, d_counts);
         }
     }
     if (hipMemcpyAsync(h_counts, d_counts, sizeof(sc_counts), hipMemcpyDeviceToHost, s) != hipSuccess) return SC_EHIP;
@@ -567,11 +498,9 @@ extern "C" int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, 
     if ((int64_t)acc != h_counts->n_pairs) return SC_EINVAL;
     SC_LAUNCH(KID_MISC, k_write_starts, dim3(1), dim3(256), 0, s, h_start, L.K3 + 1, d_offset_start);
     const int64_t tiles = (h_counts->n_out + TILE - 1) / TILE;
-    if (tiles > 0 && acc > 0) {
-        SC_LAUNCH(KID_EXPORT, k_export, dim3((unsigned)L.K3), dim3(256), 0, s,
-                           (const uint16_t*)((const char*)d_kmap + L.off_start),
-                           (const uint32_t*)((const char*)d_kmap + L.off_entries), L.sstride, L.K3, tiles,
-                           (const int32_t*)d_offset_start, d_pairs_in, d_pairs_out);
-    }
+    if (tiles > 0 && acc > 0)
+        SC_LAUNCH(KID_EXPORT, k_export, dim3((unsigned)L.K3), dim3(1024), 0, s,
+                  (const int32_t*)((const char*)d_kmap + L.off_nbr), L.K3, tiles, (const int32_t*)d_offset_start,
+                  d_pairs_in, d_pairs_out);
     return SC_OK;
 }

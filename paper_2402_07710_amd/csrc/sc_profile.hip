@@ -6,6 +6,10 @@
 
 namespace sc {
 
+#ifdef SC_TRACE
+__device__ long long* g_trace_buf = nullptr;
+#endif
+
 bool g_profile_on = false;
 
 namespace {
@@ -78,3 +82,10 @@ extern "C" int sc_profile_read(sc_profile_entry* h_entries, int max_entries) {
     }
     return n;
 }
+
+#ifdef SC_TRACE
+extern "C" int sc_trace_set(void* d_buf) {
+    long long* p = (long long*)d_buf;
+    return hipMemcpyToSymbol(HIP_SYMBOL(sc::g_trace_buf), &p, sizeof(p)) == hipSuccess ? SC_OK : SC_EHIP;
+}
+#endif

@@ -37,20 +37,22 @@ def test_counts_struct_layout():
 
 
 def test_size_queries(lib):
+    # 16-byte slots, capacity = power of two >= 4n (at least 1024)
     assert lib.sc_hash_bytes(0) == 1024 * 16
-    assert lib.sc_hash_bytes(1000) == 2048 * 16
-    assert lib.sc_hash_bytes(1024) == 2048 * 16
-    assert lib.sc_hash_bytes(1025) == 4096 * 16
+    assert lib.sc_hash_bytes(256) == 1024 * 16
+    assert lib.sc_hash_bytes(257) == 2048 * 16
+    assert lib.sc_hash_bytes(1000) == 4096 * 16
+    assert lib.sc_hash_bytes(1025) == 8192 * 16
     assert lib.sc_hash_bytes(-1) == 0
     assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
     assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
     assert lib.sc_out_bound(500, 2, 1, binding.SC_SUBM) == -1      # even K has no centre
     assert lib.sc_out_bound(500, 3, 2, binding.SC_SUBM) == -1      # submanifold stride is 1
     assert lib.sc_kmap_bytes(500, 9, 1, binding.SC_SUBM) == 0
-    # tile-major blob: header + uint16 starts + one uint32 per possible pair
+    # tile-major offset table: header + 4 mask words per tile + one int32 per (row, offset)
     b = lib.sc_kmap_bytes(6400, 3, 1, binding.SC_SUBM)
-    assert b >= 100 * 64 * 27 * 4 and b < 100 * 64 * 27 * 4 + 100 * 64 + 1024
-    assert lib.sc_kmap_scratch_bytes(6400, 2, 2, binding.SC_STRIDED) > 6400 * 8 * 4
+    assert b >= 100 * 64 * 27 * 4 + 100 * 16 and b < 100 * 64 * 27 * 4 + 100 * 16 + 1024
+    assert lib.sc_kmap_scratch_bytes(6400, 2, 2, binding.SC_STRIDED) > 32768 * 16 + 6400 * 4
     assert lib.sc_conv_workspace_bytes(3, 64, 64, binding.SC_F16) == 27 * 64 * 64 * 2
     assert lib.sc_conv_workspace_bytes(3, 16, 16, binding.SC_F32) == 0
 
