@@ -154,6 +154,154 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, v
     SC_MARK(5);
 }
 
+// ---- larger layers: W[k] streamed through LDS, one offset at a time ------------------------------
+// One wavefront per 64-row tile (four 16-row groups), four tiles per workgroup.  The workgroup
+// walks the offsets k that any of its groups needs, in lockstep.  While the matrix cores work on
+// offset k (weight tiles read from LDS, each applied to every group of the wavefront that has a
+// neighbour at k), the threads already fetch W[k'] of the next offset into registers, and as soon
+// as a 32-channel slice of the gathered rows has been used it is refilled with the rows of the
+// next offset; the offset-table lines are read two offsets ahead.  Accumulators (64 rows x C_out
+// per wavefront) never leave the registers.  KS = C_in/32, CB = C_out/16.
+template <int DT, int K3, int KS, int CB>
+__global__ void __launch_bounds__(256, 2)
+k_conv_stream(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, void* __restrict__ out, int out_f32,
+              const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
+              const sc_counts* __restrict__ counts, int64_t n_out_cap) {
+    static_assert(K3 <= 32, "one mask word per group");
+    static_assert((CB * KS) % 4 == 0, "a weight matrix is a whole number of 256-thread passes");
+    constexpr int C_in = KS * 32, C_out = CB * 16;
+    constexpr int WK = CB * KS * 64;                  // uint4 per packed W[k]
+    constexpr int WPT = WK / 256;                     // uint4 per thread per W[k]
+    extern __shared__ __align__(16) uint4 w_lds[];    // [2][WK]
+    __shared__ uint32_t bm_s;
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int r = lane & 15, qq = lane >> 4;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + wv;
+    SC_MARK(0);
+    int64_t n_out = counts->n_out;
+    if (n_out > n_out_cap) n_out = n_out_cap;
+    const bool tile_ok = tile * TILE < n_out;
+    if (threadIdx.x == 0) bm_s = 0u;
+
+    uint32_t mg0 = 0u, mg1 = 0u, mg2 = 0u, mg3 = 0u;
+    if (tile_ok) {
+        mg0 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 0]);
+        mg1 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 1]);
+        mg2 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 2]);
+        mg3 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 3]);
+    }
+    const uint32_t many = mg0 | mg1 | mg2 | mg3;
+    __syncthreads();
+    if (lane == 0 && many) atomicOr(&bm_s, many);
+    __syncthreads();
+    uint32_t todo = bm_s;                             // offsets some group of the workgroup needs
+    SC_MARK(1);
+
+    // the tile's offset-table line of offset k: lane (g, r) <- row 16g + r ... one value per group
+    const int32_t* my_nbr = nbr + tile * (int64_t)(K3 * TILE) + r;
+    auto next_offset = [&]() -> int {
+        if (!todo) return -1;
+        const int k = __builtin_ctz(todo);
+        todo &= todo - 1;
+        return k;
+    };
+    auto has = [&](int g, int k) -> bool {
+        const uint32_t m = g == 0 ? mg0 : g == 1 ? mg1 : g == 2 ? mg2 : mg3;
+        return (m >> k) & 1u;
+    };
+
+    f32x4 acc[4][CB];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) acc[g][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint4 fb[4][KS];
+    int32_t e_nxt[4] = {-1, -1, -1, -1};
+
+    int kc = next_offset(), kn = next_offset();
+    if (kc >= 0) {
+        uint4 wn[WPT];
+        int32_t e_cur[4];
+        {
+            const uint4* src = wp + (int64_t)kc * WK + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < WPT; ++i) wn[i] = src[i * 256];
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) e_cur[g] = (tile_ok && has(g, kc)) ? my_nbr[kc * TILE + g * 16] : -1;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) e_nxt[g] = (tile_ok && kn >= 0 && has(g, kn)) ? my_nbr[kn * TILE + g * 16] : -1;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint4* frow = reinterpret_cast<const uint4*>(feat + (int64_t)(e_cur[g] < 0 ? 0 : e_cur[g]) * C_in) + qq;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) fb[g][ks] = e_cur[g] >= 0 ? frow[ks * 4] : make_uint4(0, 0, 0, 0);
+        }
+        uint4* dst = w_lds + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) dst[i * 256] = wn[i];
+    }
+    __syncthreads();
+    SC_MARK(2);
+    int buf = 0;
+    while (kc >= 0) {
+        const int knn = next_offset();
+        uint4 wn[WPT];
+        {
+            const uint4* src = wp + (int64_t)(kn >= 0 ? kn : kc) * WK + threadIdx.x;   // last step: a harmless re-read
+#pragma unroll
+            for (int i = 0; i < WPT; ++i) wn[i] = src[i * 256];
+        }
+        int32_t e_nn[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) e_nn[g] = (tile_ok && knn >= 0 && has(g, knn)) ? my_nbr[knn * TILE + g * 16] : -1;
+        const uint4* wk = w_lds + buf * WK + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const uint4 a = wk[(cb * KS + ks) * 64];
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    if (has(g, kc)) acc[g][cb] = mfma16x16x32<DT>(a, fb[g][ks], acc[g][cb]);
+            }
+            if (kn >= 0) {          // this slice is free: refill it with the next offset's rows
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    if (has(g, kn)) {
+                        const uint4* frow =
+                            reinterpret_cast<const uint4*>(feat + (int64_t)(e_nxt[g] < 0 ? 0 : e_nxt[g]) * C_in) + qq;
+                        fb[g][ks] = e_nxt[g] >= 0 ? frow[ks * 4] : make_uint4(0, 0, 0, 0);
+                    }
+                }
+            }
+        }
+        {
+            uint4* dst = w_lds + (buf ^ 1) * WK + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < WPT; ++i) dst[i * 256] = wn[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < 4; ++g) e_nxt[g] = e_nn[g];
+        kc = kn; kn = knn; buf ^= 1;
+    }
+    SC_MARK(3);
+    if (tile_ok) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int64_t row = tile * TILE + g * 16 + r;
+            if (row < n_out) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) store_acc<DT>(out, out_f32, row, C_out, cb * 16 + qq * 4, acc[g][cb]);
+            }
+        }
+    }
+    SC_MARK(4);
+    SC_MARK(5);
+}
+
 // ---- any shape: weights read from global memory, offsets walked by mask bit --------------------
 // One wavefront per 16 output rows, one tile per workgroup.  C_in = 32*KS (KS <= 8),
 // C_out = 16*CB (CB <= 16), any K3 <= 343.
@@ -281,6 +429,41 @@ static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream
     return SC_OK;
 }
 
+template <int DT, int K3, int KS, int CB>
+static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
+                         const uint32_t* gmask, const int32_t* nbr, const sc_counts* counts, int64_t n_out_cap) {
+    auto fn = k_conv_stream<DT, K3, KS, CB>;
+    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return SC_EHIP;
+        attr_set = true;
+    }
+    SC_LAUNCH(KID_CONV_MFMA, fn, dim3((unsigned)((tiles + 3) / 4)), dim3(256), lds, s, feat, wp, out, out_f32, gmask,
+              nbr, counts, n_out_cap);
+    return SC_OK;
+}
+
+// Shapes with a streaming kernel.
+template <int DT>
+static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
+                           const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
+                           const sc_counts* counts, int64_t n_out_cap, bool* handled) {
+    *handled = true;
+#define SC_STREAM(K3V, KSV, CBV) \
+    return launch_stream<DT, K3V, KSV, CBV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
+    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4);
+    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8);
+    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4);
+    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8);
+    if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8);
+    if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8);
+#undef SC_STREAM
+    *handled = false;
+    return SC_OK;
+}
+
 static bool mfma_channels_ok(int C_in, int C_out) {
     return (C_in == 32 || C_in == 64 || C_in == 128 || C_in == 256) && C_out >= 16 && C_out <= 256 && C_out % 16 == 0;
 }
@@ -347,6 +530,15 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
                                          n_out_cap, &handled);
         else
             rc = launch_resident<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
+                                          (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                          n_out_cap, &handled);
+        if (handled || rc != SC_OK) return rc;
+        if (dtype_in == SC_F16)
+            rc = launch_streamed<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
+                                         (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                         n_out_cap, &handled);
+        else
+            rc = launch_streamed<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
                                           (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
                                           n_out_cap, &handled);
         if (handled || rc != SC_OK) return rc;

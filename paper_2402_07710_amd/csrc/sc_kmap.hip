@@ -36,7 +36,7 @@ k_set_n_out(sc_counts* counts, int64_t n_out) {
 // re-probes only the offsets whose slot held another key: a tile's K^3 x 64 look-ups cost a few
 // memory round trips instead of K^3.  Each wavefront then stores its offsets' 64 results as one
 // 256-byte line of the tile and votes (ballot) on which 16-row groups have a neighbour.
-template <int K, int WPT, int CH>
+template <int K, int WPT, int CH, int AT>
 __global__ void __launch_bounds__(64 * WPT)
 k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict__ slots, uint32_t mask,
             uint32_t* __restrict__ gmask, int32_t* __restrict__ nbr, sc_counts* counts, KmapHeader* hdr,
@@ -75,7 +75,7 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
         const int k_base = (p * WPT + w) * CH;
         uint32_t pending = 0;          // bit u: offset k_base+u still has to be looked up
         int32_t found[CH];
-        uint3 got[CH];
+        uint3 got[CH][AT];             // AT consecutive attempts of the probe sequence per round
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int k = k_base + u;
@@ -86,17 +86,21 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
                 if (k == centre) found[u] = (int32_t)row;                  // the centre is the row itself
                 else if (inside) pending |= 1u << u;
             }
-            got[u] = load_slot(probe_slot(key, 0, mask));   // attempt 0 of every offset at once (harmless where nothing is pending)
+            // the first AT attempts of every offset at once (harmless loads where nothing is pending)
+#pragma unroll
+            for (int a = 0; a < AT; ++a) got[u][a] = load_slot(probe_slot(key, a, mask));
         }
         SC_MARK(1);
-        for (uint32_t t = 0; __any(pending != 0); ++t) {   // ends: every probe sequence reaches an empty slot
-            if (t == 1) SC_MARK(2);
+        for (uint32_t t = 0; __any(pending != 0); t += AT) {   // ends: every probe sequence reaches an empty slot
+            if (t == AT) SC_MARK(2);
             if (t > 0) {
 #pragma unroll
                 for (int u = 0; u < CH; ++u) {
                     if (pending & (1u << u)) {
                         bool inside;
-                        got[u] = load_slot(probe_slot(neighbour_key(k_base + u, inside), t, mask));
+                        const uint64_t key = neighbour_key(k_base + u, inside);
+#pragma unroll
+                        for (int a = 0; a < AT; ++a) got[u][a] = load_slot(probe_slot(key, t + a, mask));
                     }
                 }
             }
@@ -105,9 +109,14 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
                 if (pending & (1u << u)) {
                     bool inside;
                     const uint64_t key = neighbour_key(k_base + u, inside);
-                    const uint64_t cur = (uint64_t)got[u].x | ((uint64_t)got[u].y << 32);
-                    if (cur == key) { found[u] = (int32_t)got[u].z; pending &= ~(1u << u); }
-                    else if (cur == KEY_EMPTY) pending &= ~(1u << u);
+#pragma unroll
+                    for (int a = 0; a < AT; ++a) {
+                        if (pending & (1u << u)) {
+                            const uint64_t cur = (uint64_t)got[u][a].x | ((uint64_t)got[u][a].y << 32);
+                            if (cur == key) { found[u] = (int32_t)got[u][a].z; pending &= ~(1u << u); }
+                            else if (cur == KEY_EMPTY) pending &= ~(1u << u);
+                        }
+                    }
                 }
             }
         }
@@ -414,14 +423,14 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
 
     if (mode == SC_SUBM) {
         HashTable t = table_view(const_cast<void*>(d_table), n);
-#define SC_SUBM_LAUNCH(KV, WPT, CH)                                                                               \
-    SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH>), dim3((unsigned)L.tiles), dim3(64 * WPT), 0, s,           \
+#define SC_SUBM_LAUNCH(KV, WPT, CH, AT)                                                                           \
+    SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH, AT>), dim3((unsigned)L.tiles), dim3(64 * WPT), 0, s,       \
               (const int4*)d_coords, n, (const uint4*)t.slots, t.mask, gmask, nbr, d_counts, (KmapHeader*)d_kmap, h)
         switch (K) {
-            case 1: SC_SUBM_LAUNCH(1, 1, 1); break;
-            case 3: SC_SUBM_LAUNCH(3, 8, 4); break;
-            case 5: SC_SUBM_LAUNCH(5, 8, 4); break;
-            case 7: SC_SUBM_LAUNCH(7, 8, 4); break;
+            case 1: SC_SUBM_LAUNCH(1, 1, 1, 1); break;
+            case 3: SC_SUBM_LAUNCH(3, 8, 4, 1); break;
+            case 5: SC_SUBM_LAUNCH(5, 8, 4, 1); break;
+            case 7: SC_SUBM_LAUNCH(7, 8, 4, 1); break;
             default: return SC_EINVAL;
         }
 #undef SC_SUBM_LAUNCH
