@@ -353,46 +353,63 @@ k_conv_rows16_any(const uint16_t* __restrict__ feat, const uint4* __restrict__ w
     }
 }
 
-// ---- fp32 features and weights: plain FMA ------------------------------------------------------
-// One wavefront per tile, one lane per output row; the row's accumulators live in LDS
-// ([row][channel], the lane's own line), weights are read with wavefront-uniform addresses.
-__global__ void __launch_bounds__(64)
+// ---- fp32 features and weights -------------------------------------------------------------------
+// Same scheme with the fp32 matrix instruction (v_mfma_f32_16x16x4_f32: true fp32 products and
+// sums): one wavefront per 16 output rows, offsets walked by mask bit, operands read straight from
+// the [K3][C_in][C_out] weights and the feature rows, four input channels per step.  Any C_in,
+// C_out <= 256 (edges are zero-filled).
+__global__ void __launch_bounds__(256)
 k_conv_f32(const float* __restrict__ feat, const float* __restrict__ w, float* __restrict__ out,
            const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr, int K3, int mw, int C_in, int C_out,
            const sc_counts* __restrict__ counts, int64_t n_out_cap) {
-    extern __shared__ __align__(16) float acc_lds[];      // [C_out][TILE]: channel-major, conflict-free
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int r = lane & 15, qq = lane >> 4;
+    const int CB = (C_out + 15) / 16;
     const int64_t tile = blockIdx.x;
     int64_t n_out = counts->n_out;
     if (n_out > n_out_cap) n_out = n_out_cap;
-    const int64_t row0 = tile * TILE;
-    if (row0 >= n_out) return;
-    for (int co = 0; co < C_out; ++co) acc_lds[co * TILE + lane] = 0.f;
-    const int32_t* tile_nbr = nbr + tile * (int64_t)K3 * TILE;
+    const int64_t row = tile * TILE + q * 16 + r;
+    if (tile * TILE + q * 16 >= n_out) return;                       // uniform per wavefront
+
+    f32x4 acc[CB_MAX];
+#pragma unroll
+    for (int cb = 0; cb < CB_MAX; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int32_t* line = nbr + tile * (int64_t)K3 * TILE + q * 16 + r;
     for (int wi = 0; wi < mw; ++wi) {
-        uint32_t m = 0;
-        for (int q = 0; q < 4; ++q) m |= gmask[(tile * 4 + q) * mw + wi];
+        uint32_t m = gmask[(tile * 4 + q) * mw + wi];
         while (m) {
             const int k = wi * 32 + __builtin_ctz(m);
             m &= m - 1;
-            const int32_t e = tile_nbr[(int64_t)k * TILE + lane];
-            if (e >= 0) {
-                const float* f = feat + (int64_t)e * C_in;
-                const float* wk = w + (int64_t)k * C_in * C_out;
-                for (int ci = 0; ci < C_in; ++ci) {
-                    const float fv = f[ci];
-                    for (int co = 0; co < C_out; ++co)
-                        acc_lds[co * TILE + lane] = fmaf(fv, wk[(int64_t)ci * C_out + co], acc_lds[co * TILE + lane]);
+            const int32_t e = line[(int64_t)k * TILE];
+            const float* frow = feat + (int64_t)(e < 0 ? 0 : e) * C_in;
+            const float* wk = w + (int64_t)k * C_in * C_out;
+            for (int ci0 = 0; ci0 < C_in; ci0 += 4) {
+                const int ci = ci0 + qq;
+                const bool ci_ok = ci < C_in;
+                const float b = (e >= 0 && ci_ok) ? frow[ci] : 0.f;
+#pragma unroll
+                for (int cb = 0; cb < CB_MAX; ++cb) {
+                    if (cb < CB) {
+                        const int co = cb * 16 + r;
+                        const float a = (ci_ok && co < C_out) ? wk[(int64_t)ci * C_out + co] : 0.f;
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[cb], 0, 0, 0);
+                    }
                 }
             }
         }
     }
-    __syncthreads();
-    const int rows = (int)((n_out - row0) < TILE ? (n_out - row0) : TILE);
-    float* dst = out + row0 * C_out;
-    for (int i = lane; i < rows * C_out; i += WAVE) {
-        const int rr = i / C_out, co = i - rr * C_out;
-        dst[i] = acc_lds[co * TILE + rr];
+    if (row < n_out) {
+        float* orow = out + row * C_out;
+#pragma unroll
+        for (int cb = 0; cb < CB_MAX; ++cb) {
+            if (cb < CB) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int co = cb * 16 + qq * 4 + i;
+                    if (co < C_out) orow[co] = acc[cb][i];
+                }
+            }
+        }
     }
 }
 
@@ -503,11 +520,7 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
 
     if (dtype_in == SC_F32) {
         if (C_out > 256) return SC_EINVAL;
-        const size_t lds = (size_t)TILE * C_out * sizeof(float);
-        if (lds > 48 * 1024 && hipFuncSetAttribute((const void*)k_conv_f32, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                   (int)lds) != hipSuccess)
-            return SC_EHIP;
-        SC_LAUNCH(KID_CONV_F32, k_conv_f32, dim3((unsigned)tiles), dim3(64), lds, s, (const float*)d_feat_in,
+        SC_LAUNCH(KID_CONV_F32, k_conv_f32, dim3((unsigned)tiles), dim3(256), 0, s, (const float*)d_feat_in,
                   (const float*)d_weight, (float*)d_feat_out, gmask, nbr, L.K3, L.mw, C_in, C_out, d_counts,
                   n_out_cap);
         return SC_OK;

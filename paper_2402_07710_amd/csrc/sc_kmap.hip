@@ -167,15 +167,13 @@ inline StridedScratch strided_scratch(void* p, int64_t n) {
     return s;
 }
 
-// One pass that prepares a strided build: output table <- empty, masks <- 0, offset table <- -1.
+// One pass that prepares a strided build: output table <- empty, offset table <- -1.
 __global__ void __launch_bounds__(256)
-k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, uint4* __restrict__ gmask16, int64_t mask_vec,
-               int4* __restrict__ nbr16, int64_t nbr_vec) {
+k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, int4* __restrict__ nbr16, int64_t nbr_vec) {
     const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint4 empty = make_uint4(0xffffffffu, 0xffffffffu, 0x7fffffffu, 0u);
     for (int64_t i = tid; i < (int64_t)cap; i += nthr) oslots[i] = empty;
-    for (int64_t i = tid; i < mask_vec; i += nthr) gmask16[i] = make_uint4(0u, 0u, 0u, 0u);
     for (int64_t i = tid; i < nbr_vec; i += nthr) nbr16[i] = make_int4(-1, -1, -1, -1);
 }
 
@@ -267,11 +265,11 @@ k_scan_blocks(const int32_t* __restrict__ block_sum, int32_t* __restrict__ block
 // Every input finds its output row (rank of its cell's first input among all first inputs),
 // its in-cell offset (eq. 3) and kernel offset (eq. 5), and records itself in the offset table.
 __global__ void __launch_bounds__(256)
-k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3, int mw,
+k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
                 const int32_t* __restrict__ slot_of, const uint4* __restrict__ oslots,
                 const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
-                const int32_t* __restrict__ block_prefix, uint32_t* gmask, int32_t* nbr,
-                int4* __restrict__ out_coords, sc_counts* counts, KmapHeader* hdr, KmapHeader hdr_value) {
+                const int32_t* __restrict__ block_prefix, int32_t* __restrict__ nbr,
+                int4* __restrict__ out_coords, KmapHeader* hdr, KmapHeader hdr_value) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) *hdr = hdr_value;
     if (i >= n) return;
@@ -285,10 +283,27 @@ k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3, int m
     const int k = ((c.y - qx * s) * s + (c.z - qy * s)) * s + (c.w - qz * s);
     const int64_t tile = o >> 6;
     const int j = o & 63;
-    const int32_t old = atomicExch(&nbr[(tile * K3 + k) * TILE + j], (int32_t)i);
-    if (old != -1) latch_status(counts, SC_EDUP);
-    atomicOr(&gmask[(tile * 4 + (j >> 4)) * mw + (k >> 5)], 1u << (k & 31));
+    // distinct inputs own distinct (output row, offset) cells, so a plain store is enough; repeated
+    // input coordinates are the location table's business (sc_hash_build latches SC_EDUP)
+    nbr[(tile * K3 + k) * TILE + j] = (int32_t)i;
     if (r == (int32_t)i) out_coords[o] = make_int4(c.x, qx, qy, qz);
+}
+
+// Group masks of a finished offset table: one wavefront per tile votes on every offset line.
+__global__ void __launch_bounds__(256)
+k_masks_from_table(const int32_t* __restrict__ nbr, int K3, int mw, int64_t tiles, uint32_t* __restrict__ gmask) {
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= tiles) return;
+    const int32_t* tile_nbr = nbr + tile * (int64_t)K3 * TILE;
+    for (int wi = 0; wi < mw; ++wi) {
+        uint32_t word = 0;                 // lanes 0..3: the mask word of group `lane`
+        for (int kk = 0; kk < 32 && wi * 32 + kk < K3; ++kk) {
+            const uint64_t vote = __ballot(tile_nbr[(wi * 32 + kk) * TILE + lane] >= 0);
+            if (lane < 4 && ((vote >> (16 * lane)) & 0xffffull) != 0) word |= 1u << kk;
+        }
+        if (lane < 4) gmask[(tile * 4 + lane) * mw + wi] = word;
+    }
 }
 
 // ---- reading a map back -----------------------------------------------------------------------
@@ -444,14 +459,12 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     // strided, K == stride
     StridedScratch sc_ = strided_scratch(d_scratch, n);
     const uint64_t cap = (uint64_t)sc_.omask + 1;
-    const int64_t mask_vec = (int64_t)((L.off_nbr - L.off_mask) / 16);
     const int64_t nbr_vec = (int64_t)((L.bytes - L.off_nbr) / 16);
     {
         int64_t work = (int64_t)cap > nbr_vec ? (int64_t)cap : nbr_vec;
         unsigned fb = (unsigned)((work + 255) / 256);
         if (fb > 4096) fb = 4096;
-        SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, sc_.oslots, cap, (uint4*)gmask, mask_vec,
-                  (int4*)nbr, nbr_vec);
+        SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, sc_.oslots, cap, (int4*)nbr, nbr_vec);
     }
     const int64_t nblk = (n + 1023) / 1024;
     const unsigned gb = (unsigned)((n + 255) / 256);
@@ -462,9 +475,11 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum,
               sc_.block_prefix, nblk, d_counts);
     SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
-              L.mw, (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
-              (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, gmask, nbr, (int4*)d_out_coords,
-              d_counts, (KmapHeader*)d_kmap, h);
+              (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
+              (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, nbr, (int4*)d_out_coords,
+              (KmapHeader*)d_kmap, h);
+    SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
+              (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask);
     return SC_OK;
 }
 

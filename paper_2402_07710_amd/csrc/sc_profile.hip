@@ -20,8 +20,8 @@ struct Mark {
 std::vector<Mark> g_marks;
 std::vector<hipEvent_t> g_pool;      // events ready for reuse
 const char* const KERNEL_NAMES[KID_COUNT] = {
-    "k_table_fill", "k_hash_insert", "k_hash_lookup", "k_kmap_header", "k_kmap_subm", "k_fill_i32",
-    "k_strided_insert", "k_strided_flags", "k_scan_blocks", "k_strided_pairs", "k_kmap_from_oft",
+    "k_table_fill", "k_hash_insert", "k_hash_lookup", "k_kmap_header", "k_kmap_subm", "k_strided_fill",
+    "k_strided_insert", "k_strided_flags", "k_scan_blocks", "k_strided_pairs", "k_masks_from_table",
     "k_count_pairs", "k_export", "k_weight_pack", "k_conv_mfma", "k_conv_f32", "misc"};
 
 hipEvent_t take_event() {
