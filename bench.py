@@ -29,27 +29,28 @@ PEAK_FP32_TFLOPS = 157.3       # fp32 vector ALU
 
 
 def algorithmic_bytes(kernel: str, st: dict) -> float | None:
-    """Bytes one launch of `kernel` has to move by the method's own accounting (per-unit figures
-    times units per launch; the design doc states both)."""
+    """Bytes one launch of `kernel` has to move by the method's own accounting: a per-unit figure
+    times the units one launch processes (both are stated in the design doc)."""
     N, N_out, P, K3, cap = st["N"], st["N_out"], st["P"], st["K3"], st["cap"]
     C_in, C_out, e = st["C_in"], st["C_out"], st["elem_bytes"]
     if kernel == "k_table_fill":
-        return 16.0 * cap
+        return 16.0 * cap                                  # every 16-byte slot written once
     if kernel == "k_hash_insert":
-        return N * (16 + 8 + 8 + 4)                       # coords, CAS read+write, value
+        return N * (16 + 8 + 8 + 4)                       # coords, key compare-and-swap (read + write), row index
     if kernel == "k_kmap_subm":
-        hits = P - N
-        return N * 16 + N * (K3 - 1) * 8 + hits * 4 + P * 4 + (N / 64.0) * 2 * (K3 + 1)
+        # coords, one 8-byte key per neighbour probe, 4 bytes per hit, one 4-byte table cell per (row, offset)
+        return N * 16 + N * (K3 - 1) * 8 + (P - N) * 4 + N * K3 * 4
     if kernel in ("k_conv_mfma", "k_conv_f32"):
-        return N * C_in * e + N_out * C_out * e + K3 * C_in * C_out * e + P * 4
+        # features in once, features out once, weights once, 8 bytes of map per pair
+        return N * C_in * e + N_out * C_out * e + K3 * C_in * C_out * e + P * 8
+    if kernel == "k_strided_fill":
+        return 16.0 * cap + N * K3 * 4.0
     if kernel == "k_strided_insert":
         return N * (16 + 8 + 8 + 4 + 4)
     if kernel == "k_strided_pairs":
-        return N * (16 + 4 + 4 + 4 + 8 + 4 + 4) + N_out * 16
-    if kernel == "k_kmap_from_oft":
-        return N_out * K3 * 4 + P * 4 + (N_out / 64.0) * 2 * (K3 + 1)
-    if kernel == "k_fill_i32":
-        return N * K3 * 4.0
+        return N * (16 + 4 + 16 + 4 + 4 + 8 + 4) + N_out * 16
+    if kernel == "k_masks_from_table":
+        return N_out * K3 * 4.0
     return None
 
 
@@ -60,6 +61,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", choices=["auto", "on", "off"], default="off",
+                    help="replay the step from a captured HIP graph instead of launching eagerly "
+                         "(measured slower than back-to-back eager launches here, so off by default)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run a plain device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (one process, one MI355X); run with --gpus 1",
@@ -93,6 +99,14 @@ def main() -> int:
         buf.kmap_build(d_coords, stream)
         buf.conv_fwd(d_feat, d_w, stream)
 
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     step()
     h = buf.read_counts()
     if h.status != 0:
@@ -103,12 +117,55 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+
+    # The step is a fixed sequence of kernel launches on one stream, so it can be replayed from a
+    # HIP graph: same kernels, same work, without the per-launch host cost.
+    graph = None
+    if args.graph != "off":
+        try:
+            gstream = torch.cuda.Stream()
+            gstream.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(gstream):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=gstream):
+                    buf.hash_build(d_coords, gstream)
+                    buf.kmap_build(d_coords, gstream)
+                    buf.conv_fwd(d_feat, d_w, gstream)
+            torch.cuda.synchronize()
+            ref = buf.feat_out[:N_out].clone()
+            buf.feat_out.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(ref, buf.feat_out[:N_out]):
+                raise RuntimeError("graph replay differs from the eager step")
+            graph = g
+        except Exception as exc:                                    # noqa: BLE001
+            if args.graph == "on":
+                raise
+            print(f"bench.py: graph capture unavailable ({exc}); timing eager launches", file=sys.stderr)
+            torch.cuda.synchronize()
+
+    def timed_step():
+        if graph is not None:
+            graph.replay()
+        else:
+            step()
+
+    for _ in range(args.warmup):
+        timed_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        timed_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step_eager = (time.perf_counter() - t0) * 1e3 / args.steps
     value = flops / (ms_per_step * 1e-3) / 1e12
 
     # per-phase split with torch events (the library launches on torch's current stream)
@@ -125,18 +182,18 @@ def main() -> int:
     phases = {name: float(np.median([e[j].elapsed_time(e[j + 1]) for e in ev]))
               for j, name in enumerate(["hash_ms", "kmap_ms", "conv_ms"])}
 
-    # per-kernel durations: HIP events around every launch, recorded by the library itself on
-    # the launch stream, over the same number of steps
+    # per-kernel durations: every launch carries a pair of HIP events stamped with the dispatch's
+    # begin and end (hipExtLaunchKernelGGL inside the library), over the same number of steps
     sc.sc_profile_enable(True)
     for _ in range(args.steps):
         step()
     prof = sc.sc_profile_read()
     sc.sc_profile_enable(False)
     kernels = {name: {"launches": l, "avg_us": 1e3 * ms / l} for name, (l, ms) in prof.items()}
-    per_step_us = {name: 1e3 * ms / args.steps for name, (l, ms) in prof.items()}
+    per_step_us = {name: kernels[name]["avg_us"] * l / args.steps for name, (l, ms) in prof.items()}
     dominant = max(per_step_us, key=per_step_us.get)
     launches_per_step = prof[dominant][0] / args.steps
-    avg_s = prof[dominant][1] * 1e-3 / prof[dominant][0]
+    avg_s = kernels[dominant]["avg_us"] * 1e-6
     st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=sc.sc_hash_bytes(N) // 16, C_in=C_in, C_out=C_out,
               elem_bytes=d_feat.element_size())
     traffic = None
@@ -174,6 +231,7 @@ def main() -> int:
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": args.workload, "mode": mode, "K": K, "stride": stride, "C_in": C_in,
                    "C_out": C_out, "N": N, "N_out": N_out, "P": P, "pairs_per_voxel": P / max(N, 1)},
+        "launch": "hip graph replay" if graph is not None else "eager", "ms_per_step_eager": ms_per_step_eager,
         "phases_ms": phases, "kernels": per_kernel, "roofline": roofline,
     }
 

@@ -179,12 +179,12 @@ const char* sc_strerror(int status);
 /* ---- measurement aid (not part of the paper's method) -------------------------------------- */
 
 /* Per-kernel timing for benchmarks.  sc_profile_enable(1) clears earlier samples and makes every
- * later call of this library record a pair of HIP events around each kernel it launches, on the
- * launch's own stream; sc_profile_enable(0) stops that.  sc_profile_read synchronises the device
+ * later call of this library attach a pair of HIP events to each kernel it launches (stamped with
+ * the dispatch's own begin and end times); sc_profile_enable(0) stops that.  sc_profile_read synchronises the device
  * and fills up to max_entries entries (one per kernel that ran: name, number of launches, summed
  * duration in ms); it returns the number of entries written or a negative SC_E* code.  `name`
  * points to a static string.  This is process-wide state for single-threaded measurement code;
- * it is off by default and the timed events add a little latency between kernels while on. */
+ * it is off by default. */
 typedef struct sc_profile_entry {
     const char* name;
     int64_t launches;
@@ -192,6 +192,7 @@ typedef struct sc_profile_entry {
 } sc_profile_entry;
 int sc_profile_enable(int enable);
 int sc_profile_read(sc_profile_entry* h_entries, int max_entries);
+
 
 #ifdef __cplusplus
 }

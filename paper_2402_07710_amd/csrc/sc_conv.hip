@@ -82,11 +82,12 @@ __device__ inline void store_acc(void* __restrict__ out, int out_f32, int64_t ro
 
 // ---- small layers: all of W resident in LDS ----------------------------------------------------
 // One wavefront per 16 output rows, NT tiles (4*NT wavefronts) per workgroup.  The workgroup
-// copies the packed weights of all K3 offsets into LDS once; meanwhile every wavefront has its
-// K3 offset-table lines and then all its feature gathers in flight.  KS = C_in/32, CB = C_out/16.
+// copies the weights of all K3 offsets into LDS once, re-laying them out as MFMA operand tiles on
+// the way, so no separate packing pass is needed; meanwhile every wavefront has its K3 offset-table lines and then all its feature
+// gathers in flight.  KS = C_in/32, CB = C_out/16.
 template <int DT, int K3, int KS, int CB, int NT>
 __global__ void __launch_bounds__(256 * NT)
-k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, void* __restrict__ out, int out_f32,
+k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw, void* __restrict__ out, int out_f32,
               const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
               const sc_counts* __restrict__ counts, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
@@ -94,7 +95,7 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, v
     extern __shared__ __align__(16) uint4 w_lds[];                   // [K3][CB][KS][64]
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
-    const int64_t tile = (int64_t)blockIdx.x * NT + (wv >> 2);
+    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NT + (wv >> 2);
     const int q = wv & 3;
     SC_MARK(0);
     int64_t n_out = counts->n_out;
@@ -114,8 +115,24 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, v
 #pragma unroll
         for (int k = 0; k < K3; ++k) e[k] = -1;
     }
-    // weights -> LDS (every thread helps, also wavefronts without rows)
-    for (int i = threadIdx.x; i < K3 * CB * KS * 64; i += 256 * NT) w_lds[i] = wp[i];
+    // weights -> LDS as operand tiles (every thread helps, also wavefronts without rows): the
+    // thread that fills (tile, lane) reads its 8 input channels of one output channel (2-byte
+    // loads, 128 contiguous bytes per wavefront) and writes them as one 16-byte LDS store
+    {
+        const uint16_t* w16 = reinterpret_cast<const uint16_t*>(wraw);
+        for (int i = threadIdx.x; i < K3 * CB * KS * 64; i += 256 * NT) {
+            const int ln = i & 63;
+            int rest = i >> 6;
+            const int ks = rest % KS; rest /= KS;
+            const int cb = rest % CB;
+            const int k = rest / CB;
+            const uint16_t* src = w16 + ((int64_t)k * C_in + ks * 32 + 8 * (ln >> 4)) * C_out + cb * 16 + (ln & 15);
+            uint32_t v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (uint32_t)src[(2 * j) * C_out] | ((uint32_t)src[(2 * j + 1) * C_out] << 16);
+            w_lds[i] = make_uint4(v[0], v[1], v[2], v[3]);
+        }
+    }
     SC_MARK(1);
     m = __builtin_amdgcn_readfirstlane(m);
 
@@ -177,7 +194,7 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, v
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + wv;
+    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * 4 + wv;
     SC_MARK(0);
     int64_t n_out = counts->n_out;
     if (n_out > n_out_cap) n_out = n_out_cap;
@@ -424,7 +441,7 @@ static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, con
             return SC_EHIP;
         attr_set = true;
     }
-    const dim3 grid((unsigned)((tiles + NT - 1) / NT));
+    const dim3 grid(xcd_grid((tiles + NT - 1) / NT));
     SC_LAUNCH(KID_CONV_MFMA, fn, grid, dim3(256 * NT), lds, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
     return SC_OK;
 }
@@ -457,7 +474,7 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
             return SC_EHIP;
         attr_set = true;
     }
-    SC_LAUNCH(KID_CONV_MFMA, fn, dim3((unsigned)((tiles + 3) / 4)), dim3(256), lds, s, feat, wp, out, out_f32, gmask,
+    SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + 3) / 4)), dim3(256), lds, s, feat, wp, out, out_f32, gmask,
               nbr, counts, n_out_cap);
     return SC_OK;
 }
@@ -529,23 +546,27 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
     if (!mfma_channels_ok(C_in, C_out)) return SC_EINVAL;
     const size_t need = sc_conv_workspace_bytes(K, C_in, C_out, dtype_in);
     if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
-    const int64_t pack_threads = (int64_t)L.K3 * (C_out / 16) * (C_in / 32) * 64;
-    SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
-              (const uint16_t*)d_weight, (uint4*)d_workspace, L.K3, C_in, C_out);
     const int out_f32 = dtype_out == SC_F32;
     static const bool force_any = getenv("SC_CONV_GENERIC") != nullptr;
-    if (!force_any) {
+    if (!force_any) {           // small layers: weights go to LDS straight from d_weight
         bool handled = false;
         int rc;
         if (dtype_in == SC_F16)
             rc = launch_resident<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                         (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                         (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, d_counts,
                                          n_out_cap, &handled);
         else
             rc = launch_resident<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                          (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                          (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, d_counts,
                                           n_out_cap, &handled);
         if (handled || rc != SC_OK) return rc;
+    }
+    const int64_t pack_threads = (int64_t)L.K3 * (C_out / 16) * (C_in / 32) * 64;
+    SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
+              (const uint16_t*)d_weight, (uint4*)d_workspace, L.K3, C_in, C_out);
+    if (!force_any) {
+        bool handled = false;
+        int rc;
         if (dtype_in == SC_F16)
             rc = launch_streamed<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
                                          (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,

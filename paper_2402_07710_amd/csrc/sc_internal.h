@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdlib.h>
 
@@ -125,6 +126,18 @@ inline KmapLayout kmap_layout(int64_t n_out_bound, int K) {
     return L;
 }
 
+// Workgroup -> work unit, XCD-aware.  MI355X hands consecutive workgroups to its 8 XCDs in turn
+// and every XCD has its own L2.  Units (tiles of consecutive rows) that are close in index are
+// close in space, so each XCD is given one contiguous eighth of the units: the slice of the
+// location table and of the feature rows it touches is then fetched into one L2, not eight.
+// Launch xcd_grid(units) workgroups; a workgroup whose unit is >= units has nothing to do.
+constexpr int NUM_XCD = 8;
+inline unsigned xcd_grid(int64_t units) { return (unsigned)((units + NUM_XCD - 1) / NUM_XCD * NUM_XCD); }
+__device__ inline int64_t xcd_unit(unsigned block, unsigned grid) {
+    const unsigned chunk = grid / NUM_XCD;
+    return (int64_t)(block % NUM_XCD) * chunk + block / NUM_XCD;
+}
+
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 #define SC_HIP_CHECK_LAUNCH()                        \
@@ -152,15 +165,20 @@ enum KernelId {
     KID_COUNT_PAIRS, KID_EXPORT, KID_WEIGHT_PACK, KID_CONV_MFMA, KID_CONV_F32, KID_MISC, KID_COUNT
 };
 extern bool g_profile_on;
-void profile_mark(int kernel_id, hipStream_t s, bool after);
+// A fresh pair of events for one launch of `kernel_id`; false if none could be created.
+bool profile_events(int kernel_id, hipEvent_t* begin, hipEvent_t* end);
 
-// Launch a kernel; when profiling is on, bracket it with a pair of HIP events on the same stream.
-#define SC_LAUNCH(kid, kernel, grid, block, lds, stream, ...)                    \
-    do {                                                                         \
-        if (sc::g_profile_on) sc::profile_mark(kid, stream, false);              \
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);       \
-        if (sc::g_profile_on) sc::profile_mark(kid, stream, true);               \
-        if (hipGetLastError() != hipSuccess) return SC_EHIP;                     \
+// Launch a kernel.  When profiling is on, the launch carries a pair of events that the runtime
+// stamps with the dispatch's own begin and end times (hipExtLaunchKernelGGL), the same clock a
+// profiler's kernel trace reports.
+#define SC_LAUNCH(kid, kernel, grid, block, lds, stream, ...)                                      \
+    do {                                                                                           \
+        hipEvent_t sc_ev0_, sc_ev1_;                                                               \
+        if (sc::g_profile_on && sc::profile_events(kid, &sc_ev0_, &sc_ev1_))                       \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, sc_ev0_, sc_ev1_, 0, __VA_ARGS__); \
+        else                                                                                       \
+            hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                     \
+        if (hipGetLastError() != hipSuccess) return SC_EHIP;                                       \
     } while (0)
 
 }  // namespace sc

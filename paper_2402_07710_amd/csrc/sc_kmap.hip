@@ -48,8 +48,9 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
     __shared__ uint32_t mask_s[4 * MW];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t tile = blockIdx.x;
+    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x);
     SC_MARK(0);
+    if (tile * TILE >= n) return;                    // padding workgroup of the XCD-aware grid
     if (threadIdx.x < 4 * MW) mask_s[threadIdx.x] = 0u;
     const int64_t row = tile * TILE + lane;
     const bool valid = row < n;
@@ -439,7 +440,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     if (mode == SC_SUBM) {
         HashTable t = table_view(const_cast<void*>(d_table), n);
 #define SC_SUBM_LAUNCH(KV, WPT, CH, AT)                                                                           \
-    SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH, AT>), dim3((unsigned)L.tiles), dim3(64 * WPT), 0, s,       \
+    SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH, AT>), dim3(xcd_grid(L.tiles)), dim3(64 * WPT), 0, s,      \
               (const int4*)d_coords, n, (const uint4*)t.slots, t.mask, gmask, nbr, d_counts, (KmapHeader*)d_kmap, h)
         switch (K) {
             case 1: SC_SUBM_LAUNCH(1, 1, 1, 1); break;

@@ -1,5 +1,6 @@
-// Optional per-kernel timing: a pair of HIP events around every launch, on the launch's own
-// stream, so a benchmark can report the duration of each kernel without an external profiler.
+// Optional per-kernel timing: every launch carries a pair of HIP events stamped with the
+// dispatch's begin and end, so a benchmark can report the duration of each kernel without an
+// external profiler.
 #include <vector>
 
 #include "sc_internal.h"
@@ -36,15 +37,13 @@ hipEvent_t take_event() {
 }
 }  // namespace
 
-void profile_mark(int kernel_id, hipStream_t s, bool after) {
-    if (!after) {
-        Mark m{kernel_id, take_event(), take_event()};
-        if (m.begin == nullptr || m.end == nullptr) return;
-        (void)hipEventRecord(m.begin, s);
-        g_marks.push_back(m);
-    } else if (!g_marks.empty() && g_marks.back().kid == kernel_id) {
-        (void)hipEventRecord(g_marks.back().end, s);
-    }
+bool profile_events(int kernel_id, hipEvent_t* begin, hipEvent_t* end) {
+    Mark m{kernel_id, take_event(), take_event()};
+    if (m.begin == nullptr || m.end == nullptr) return false;
+    g_marks.push_back(m);
+    *begin = m.begin;
+    *end = m.end;
+    return true;
 }
 
 }  // namespace sc
