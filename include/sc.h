@@ -102,17 +102,20 @@ size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode);
 
 /* Build the kernel map.
  *   d_table       table built by sc_hash_build over the same d_coords (required for SC_SUBM;
- *                 ignored for SC_STRIDED with K == stride, may be NULL there)
+ *                 ignored for SC_STRIDED with K == stride, may be NULL there - but repeated
+ *                 input coordinates are only detected by sc_hash_build)
  *   mode          SC_SUBM (stride must be 1, K odd, K <= SC_K_MAX) or SC_STRIDED (K == stride,
  *                 2 <= K <= 4; other K/stride combinations return SC_EINVAL)
  *   d_out_coords  [sc_out_bound][4]; receives the output coordinates.  SC_SUBM: may be NULL
  *                 (outputs are the inputs, same order).  SC_STRIDED: required; output o is the
  *                 o-th distinct cell in order of first occurrence in the input, so the result
  *                 does not depend on thread timing.
- *   d_kmap        opaque blob, kmap_bytes >= sc_kmap_bytes(...).  Layout (tile-major): outputs
- *                 are cut into tiles of 64 consecutive rows; each tile holds its pairs grouped
- *                 by offset k, ordered by output row inside one offset.  Read it with
- *                 sc_kmap_export; feed it to sc_conv_fwd.
+ *   d_kmap        opaque blob, kmap_bytes >= sc_kmap_bytes(...).  It holds the offset table of
+ *                 Section III-C.2 (for every output row and offset the paired input row or -1),
+ *                 tile-major: 64 consecutive output rows per tile, offset-major inside a tile,
+ *                 plus one bit per (16-row group, offset) that tells whether the group has any
+ *                 neighbour there.  Read it with sc_kmap_export; feed it to sc_conv_fwd (any
+ *                 number of times: layers that share coordinates share the map).
  *   d_scratch     scratch_bytes >= sc_kmap_scratch_bytes(...); contents undefined afterwards.
  *   d_counts      n_out is written here (device side); errors are latched into status. */
 int sc_kmap_build(const int32_t* d_coords, int64_t n,
@@ -125,7 +128,8 @@ int sc_kmap_build(const int32_t* d_coords, int64_t n,
 
 /* ---- compute (Algorithm 2; Section III-C.3) ---------------------------------------------- */
 
-/* Workspace sc_conv_fwd needs for the given layer (re-laid-out weights); may be 0. */
+/* Workspace sc_conv_fwd may use for the given layer (weights re-laid out as MFMA operand tiles
+ * when they do not fit in LDS as a whole); 0 for fp32 layers. */
 size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_in);
 
 /* d_feat_out[o][:] = sum over offsets k and pairs (i,o) of d_feat_in[i][:] . d_weight[k]
@@ -135,7 +139,7 @@ size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_in);
  *               with no pair becomes 0), rows >= n_out are left untouched.  n_out is read on
  *               the device from d_counts; n_out_cap >= sc_out_bound(...) is always enough.
  *   d_kmap      blob from sc_kmap_build for the same (n_in, K, stride, mode)
- *   dtype_in    SC_F32 (plain fp32 FMA) or SC_F16 / SC_BF16 (MFMA, fp32 accumulation)
+ *   dtype_in    SC_F32 (fp32 MFMA) or SC_F16 / SC_BF16 (16-bit MFMA, fp32 accumulation)
  *   dtype_out   SC_F32 or the same as dtype_in (one round-to-nearest-even at the end)
  *   channels    SC_F32: any C_in >= 1, 1 <= C_out <= 256.  SC_F16 / SC_BF16: C_in one of 32, 64,
  *               128, 256 and C_out a multiple of 16, 16 <= C_out <= 256.
@@ -161,9 +165,9 @@ int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts,
 
 /* Rulebook in its plain form, for inspection and tests: pairs grouped by offset,
  * d_pairs_in / d_pairs_out [n_pairs] and d_offset_start [K^3+1] (int32, device memory; pairs of
- * offset k are [offset_start[k], offset_start[k+1])).  The order of pairs inside one offset is
- * unspecified.  h_counts must come from sc_counts_read on the same map (it gives the sizes).
- * Asynchronous on `stream`. */
+ * offset k are [offset_start[k], offset_start[k+1])), ordered by output row inside one offset
+ * (ballot + prefix-count compaction of the offset table).  h_counts must come from
+ * sc_counts_read on the same map (it gives the sizes).  Asynchronous on `stream`. */
 int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, int mode,
                    const sc_counts* h_counts,
                    int32_t* d_pairs_in, int32_t* d_pairs_out, int32_t* d_offset_start,
@@ -180,8 +184,8 @@ const char* sc_strerror(int status);
 
 /* Per-kernel timing for benchmarks.  sc_profile_enable(1) clears earlier samples and makes every
  * later call of this library attach a pair of HIP events to each kernel it launches (stamped with
- * the dispatch's own begin and end times); sc_profile_enable(0) stops that.  sc_profile_read synchronises the device
- * and fills up to max_entries entries (one per kernel that ran: name, number of launches, summed
+ * the dispatch's own begin and end times); sc_profile_enable(0) stops that.  sc_profile_read
+ * synchronises the device and fills up to max_entries entries (one per kernel that ran: name, number of launches, summed
  * duration in ms); it returns the number of entries written or a negative SC_E* code.  `name`
  * points to a static string.  This is process-wide state for single-threaded measurement code;
  * it is off by default. */
@@ -192,7 +196,6 @@ typedef struct sc_profile_entry {
 } sc_profile_entry;
 int sc_profile_enable(int enable);
 int sc_profile_read(sc_profile_entry* h_entries, int max_entries);
-
 
 #ifdef __cplusplus
 }
