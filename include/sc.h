@@ -56,6 +56,7 @@ extern "C" {
 /* layer kinds */
 #define SC_SUBM      0     /* submanifold: outputs = inputs, stride 1, K odd (Section II-B) */
 #define SC_STRIDED   1     /* "normal" down-sampling sparse convolution (Section III-B, III-D) */
+#define SC_INVERSE   2     /* inverse (up-sampling) convolution (Section III-E); maps come from sc_kmap_transpose */
 
 /* element types of features and weights */
 #define SC_F32       0
@@ -93,7 +94,8 @@ int sc_hash_build(const int32_t* d_coords, int64_t n,
  * Section III-D for strided layers: cell index floor(p/s), in-cell offset, distinct output
  * cells counted and numbered) ------------------------------------------------------------- */
 
-/* Upper bound on output rows for n inputs: n for SC_SUBM and for SC_STRIDED with K == stride. */
+/* Upper bound on output rows for n inputs: n for SC_SUBM and for SC_STRIDED with K == stride
+ * (for SC_INVERSE: the n fine rows themselves). */
 int64_t sc_out_bound(int64_t n, int K, int stride, int mode);
 
 /* Bytes of the kernel-map blob and of the scratch buffer sc_kmap_build needs (0 = unsupported). */
@@ -126,6 +128,21 @@ int sc_kmap_build(const int32_t* d_coords, int64_t n,
                   void* d_scratch, size_t scratch_bytes,
                   sc_counts* d_counts, void* stream);
 
+/* Inverse (up-sampling) layer, Section III-E: every row of the fine set finds its parent in the
+ * coarse set and its place in the kernel, and receives parent_features . W[place].  The pairs are
+ * those of the strided layer that made the coarse set, with input and output swapped, so the map
+ * is made from that layer's map:
+ *   d_kmap, n, K, stride   the strided layer's map and the arguments it was built with
+ *   d_counts               the counts block of that build (n_out is read on the device)
+ *   d_kmap_inv             receives the inverse map, kmap_inv_bytes >= sc_kmap_bytes(n, K,
+ *                          stride, SC_INVERSE); must not alias d_kmap
+ * Use it with sc_conv_fwd(mode = SC_INVERSE): d_feat_in has one row per coarse cell, d_feat_out
+ * one row per fine row (n of them), W[k] is applied to the pair whose fine row sits at in-cell
+ * offset k.  sc_counts_read / sc_kmap_export accept the inverse map with mode = SC_INVERSE. */
+int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int stride,
+                      const sc_counts* d_counts,
+                      void* d_kmap_inv, size_t kmap_inv_bytes, void* stream);
+
 /* ---- compute (Algorithm 2; Section III-C.3) ---------------------------------------------- */
 
 /* Workspace sc_conv_fwd may use for the given layer (weights re-laid out as MFMA operand tiles
@@ -133,18 +150,20 @@ int sc_kmap_build(const int32_t* d_coords, int64_t n,
 size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_in);
 
 /* d_feat_out[o][:] = sum over offsets k and pairs (i,o) of d_feat_in[i][:] . d_weight[k]
- *   d_feat_in   [n_in][C_in]  of dtype_in
+ *   n_map       the n the kernel map was built with (rows of d_feat_in for SC_SUBM / SC_STRIDED;
+ *               rows of d_feat_out for SC_INVERSE)
+ *   d_feat_in   [rows][C_in]  of dtype_in
  *   d_weight    [K^3][C_in][C_out] of dtype_in
  *   d_feat_out  [n_out_cap][C_out] of dtype_out; rows [0, n_out) are fully overwritten (a row
  *               with no pair becomes 0), rows >= n_out are left untouched.  n_out is read on
  *               the device from d_counts; n_out_cap >= sc_out_bound(...) is always enough.
- *   d_kmap      blob from sc_kmap_build for the same (n_in, K, stride, mode)
+ *   d_kmap      blob from sc_kmap_build (or sc_kmap_transpose) for the same (n_map, K, stride)
  *   dtype_in    SC_F32 (fp32 MFMA) or SC_F16 / SC_BF16 (16-bit MFMA, fp32 accumulation)
  *   dtype_out   SC_F32 or the same as dtype_in (one round-to-nearest-even at the end)
  *   channels    SC_F32: any C_in >= 1, 1 <= C_out <= 256.  SC_F16 / SC_BF16: C_in one of 32, 64,
  *               128, 256 and C_out a multiple of 16, 16 <= C_out <= 256.
  *   d_workspace workspace_bytes >= sc_conv_workspace_bytes(...); contents undefined afterwards */
-int sc_conv_fwd(const void* d_feat_in, int64_t n_in,
+int sc_conv_fwd(const void* d_feat_in, int64_t n_map,
                 const void* d_weight,
                 void* d_feat_out, int64_t n_out_cap,
                 const void* d_kmap, size_t kmap_bytes,

@@ -119,6 +119,22 @@ def sparse_conv(coords, feat_in, weight, K, stride, mode, threads=1):
     return default().sparse_conv(coords, feat_in, weight, K, stride, mode, threads)
 
 
+def transpose_map(km: dict) -> dict:
+    """Kernel map of the inverse (up-sampling) layer of Section III-E: the same pairs with input
+    and output swapped (a fine row receives from its coarse parent through W[k], k = the fine
+    row's place in the kernel).  Inside one offset the pairs are ordered by the new output row."""
+    ost = np.asarray(km["offset_start"])
+    pin = np.empty_like(km["pair_in"])
+    pout = np.empty_like(km["pair_out"])
+    for k in range(len(ost) - 1):
+        sl = slice(ost[k], ost[k + 1])
+        order = np.argsort(km["pair_in"][sl], kind="stable")
+        pin[sl] = km["pair_out"][sl][order]
+        pout[sl] = km["pair_in"][sl][order]
+    return dict(K=km["K"], stride=km["stride"], mode=km["mode"], n_in=km["n_out"], n_out=km["n_in"],
+                out_coords=None, pair_in=pin, pair_out=pout, offset_start=ost.copy())
+
+
 def canonical_pairs(km: dict):
     """Order-independent form of a kernel map: output sites sorted by (b,x,y,z) and renumbered,
     then every offset's pairs sorted by (out, in).  Returns (sorted out_coords, list of [P_k,2]

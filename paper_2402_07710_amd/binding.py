@@ -15,17 +15,18 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SC_LIB_PATH", os.path.join(HERE, "libsc.so"))   # override: development builds
 
 SC_OK, SC_EINVAL, SC_ERANGE, SC_EDUP, SC_ECAP, SC_EHIP, SC_EFULL = 0, -1, -2, -3, -4, -5, -6
-SC_SUBM, SC_STRIDED = 0, 1
+SC_SUBM, SC_STRIDED, SC_INVERSE = 0, 1, 2
 SC_F32, SC_F16, SC_BF16 = 0, 1, 2
 SC_COORD_MAX, SC_N_MAX, SC_K_MAX = 65534, 1 << 26, 7
-MODES = {"subm": SC_SUBM, "strided": SC_STRIDED, SC_SUBM: SC_SUBM, SC_STRIDED: SC_STRIDED}
+MODES = {"subm": SC_SUBM, "strided": SC_STRIDED, "inverse": SC_INVERSE,
+         SC_SUBM: SC_SUBM, SC_STRIDED: SC_STRIDED, SC_INVERSE: SC_INVERSE}
 DTYPES = {"f32": SC_F32, "f16": SC_F16, "bf16": SC_BF16,
           torch.float32: SC_F32, torch.float16: SC_F16, torch.bfloat16: SC_BF16}
 TORCH_DTYPES = {SC_F32: torch.float32, SC_F16: torch.float16, SC_BF16: torch.bfloat16}
 
 # every symbol include/sc.h declares
 SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
-           "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_conv_workspace_bytes", "sc_conv_fwd",
+           "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read"]
 
 
@@ -70,6 +71,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_kmap_bytes": (sz, [i64, i32, i32, i32]),
         "sc_kmap_scratch_bytes": (sz, [i64, i32, i32, i32]),
         "sc_kmap_build": (i32, [vp, i64, vp, i32, i32, i32, vp, vp, sz, vp, sz, vp, vp]),
+        "sc_kmap_transpose": (i32, [vp, i64, i32, i32, vp, vp, sz, vp]),
         "sc_conv_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "sc_conv_fwd": (i32, [vp, i64, vp, vp, i64, vp, sz, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
         "sc_counts_read": (i32, [vp, ctypes.POINTER(ScCounts), vp, i64, i32, i32, i32, vp]),
@@ -151,13 +153,21 @@ def sc_kmap_build(coords, table, K, stride, mode, out_coords, kmap, scratch, cou
                                 _ptr(counts), _stream(stream)), "sc_kmap_build")
 
 
-def sc_conv_fwd(feat_in, weight, feat_out, kmap, counts, K, stride, mode, workspace=None, stream=None):
-    """feat_in [n_in,C_in], weight [K^3,C_in,C_out] (same dtype), feat_out [n_out_cap,C_out]."""
+def sc_kmap_transpose(kmap, n, K, stride, counts, kmap_inv, stream=None):
+    _check(load().sc_kmap_transpose(_ptr(kmap), n, K, stride, _ptr(counts), _ptr(kmap_inv),
+                                    kmap_inv.numel() * kmap_inv.element_size(), _stream(stream)), "sc_kmap_transpose")
+
+
+def sc_conv_fwd(feat_in, weight, feat_out, kmap, counts, K, stride, mode, workspace=None, stream=None, n_map=None):
+    """feat_in [rows,C_in], weight [K^3,C_in,C_out] (same dtype), feat_out [n_out_cap,C_out];
+    n_map = the n the map was built with (default: rows of feat_in)."""
     n_in, C_in = feat_in.shape
     n_out_cap, C_out = feat_out.shape
+    if n_map is None:
+        n_map = n_in
     if tuple(weight.shape) != (K ** 3, C_in, C_out) or weight.dtype != feat_in.dtype:
         raise ValueError("weight must be [K^3, C_in, C_out] in the feature dtype")
-    _check(load().sc_conv_fwd(_ptr(feat_in), n_in, _ptr(weight), _ptr(feat_out), n_out_cap, _ptr(kmap),
+    _check(load().sc_conv_fwd(_ptr(feat_in), n_map, _ptr(weight), _ptr(feat_out), n_out_cap, _ptr(kmap),
                               kmap.numel() * kmap.element_size(), _ptr(counts), K, stride, MODES[mode],
                               C_in, C_out, DTYPES[feat_in.dtype], DTYPES[feat_out.dtype], _ptr(workspace),
                               0 if workspace is None else workspace.numel() * workspace.element_size(),

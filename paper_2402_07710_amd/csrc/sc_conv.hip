@@ -89,7 +89,7 @@ template <int DT, int K3, int KS, int CB, int NT>
 __global__ void __launch_bounds__(256 * NT)
 k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw, void* __restrict__ out, int out_f32,
               const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
-              const sc_counts* __restrict__ counts, int64_t n_out_cap) {
+              const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
     constexpr int C_in = KS * 32, C_out = CB * 16;
     extern __shared__ __align__(16) uint4 w_lds[];                   // [K3][CB][KS][64]
@@ -98,7 +98,7 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NT + (wv >> 2);
     const int q = wv & 3;
     SC_MARK(0);
-    int64_t n_out = counts->n_out;
+    int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
     const int64_t row = tile * TILE + q * 16 + r;
     const bool group_ok = tile * TILE + q * 16 < n_out;             // uniform per wavefront
@@ -183,7 +183,7 @@ template <int DT, int K3, int KS, int CB>
 __global__ void __launch_bounds__(256, 2)
 k_conv_stream(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, void* __restrict__ out, int out_f32,
               const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
-              const sc_counts* __restrict__ counts, int64_t n_out_cap) {
+              const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
     static_assert((CB * KS) % 4 == 0, "a weight matrix is a whole number of 256-thread passes");
     constexpr int C_in = KS * 32, C_out = CB * 16;
@@ -196,7 +196,7 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, v
     const int r = lane & 15, qq = lane >> 4;
     const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * 4 + wv;
     SC_MARK(0);
-    int64_t n_out = counts->n_out;
+    int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
     const bool tile_ok = tile * TILE < n_out;
     if (threadIdx.x == 0) bm_s = 0u;
@@ -327,12 +327,12 @@ template <int DT>
 __global__ void __launch_bounds__(256)
 k_conv_rows16_any(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, void* __restrict__ out,
                   int out_f32, const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr, int K3, int mw,
-                  int KS, int CB, const sc_counts* __restrict__ counts, int64_t n_out_cap) {
+                  int KS, int CB, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     const int C_in = KS * 32, C_out = CB * 16;
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
     const int64_t tile = blockIdx.x;
-    int64_t n_out = counts->n_out;
+    int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
     const int64_t row = tile * TILE + q * 16 + r;
     if (tile * TILE + q * 16 >= n_out) return;                       // uniform per wavefront
@@ -378,12 +378,12 @@ k_conv_rows16_any(const uint16_t* __restrict__ feat, const uint4* __restrict__ w
 __global__ void __launch_bounds__(256)
 k_conv_f32(const float* __restrict__ feat, const float* __restrict__ w, float* __restrict__ out,
            const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr, int K3, int mw, int C_in, int C_out,
-           const sc_counts* __restrict__ counts, int64_t n_out_cap) {
+           const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
     const int CB = (C_out + 15) / 16;
     const int64_t tile = blockIdx.x;
-    int64_t n_out = counts->n_out;
+    int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
     const int64_t row = tile * TILE + q * 16 + r;
     if (tile * TILE + q * 16 >= n_out) return;                       // uniform per wavefront
@@ -432,7 +432,7 @@ k_conv_f32(const float* __restrict__ feat, const float* __restrict__ w, float* _
 
 template <int DT, int K3, int KS, int CB, int NT>
 static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
-                         const uint32_t* gmask, const int32_t* nbr, const sc_counts* counts, int64_t n_out_cap) {
+                         const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
     auto fn = k_conv_rows16<DT, K3, KS, CB, NT>;
     const size_t lds = (size_t)K3 * CB * KS * 64 * sizeof(uint4);
     static bool attr_set = false;           // once per instantiation; the value never changes
@@ -450,7 +450,7 @@ static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, con
 template <int DT>
 static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
                            const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
-                           const sc_counts* counts, int64_t n_out_cap, bool* handled) {
+                           const int64_t* counts, int64_t n_out_cap, bool* handled) {
     *handled = true;
 #define SC_ROWS16(K3V, KSV, CBV, NTV) \
     return launch_rows16<DT, K3V, KSV, CBV, NTV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
@@ -465,7 +465,7 @@ static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream
 
 template <int DT, int K3, int KS, int CB>
 static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
-                         const uint32_t* gmask, const int32_t* nbr, const sc_counts* counts, int64_t n_out_cap) {
+                         const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
     auto fn = k_conv_stream<DT, K3, KS, CB>;
     const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4);
     static bool attr_set = false;
@@ -483,7 +483,7 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
 template <int DT>
 static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
                            const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
-                           const sc_counts* counts, int64_t n_out_cap, bool* handled) {
+                           const int64_t* counts, int64_t n_out_cap, bool* handled) {
     *handled = true;
 #define SC_STREAM(K3V, KSV, CBV) \
     return launch_stream<DT, K3V, KSV, CBV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
@@ -512,21 +512,23 @@ extern "C" size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_
     return align_up((size_t)K * K * K * C_in * C_out * 2, 256);
 }
 
-extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_weight, void* d_feat_out,
+extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_weight, void* d_feat_out,
                            int64_t n_out_cap, const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts, int K,
                            int stride, int mode, int C_in, int C_out, int dtype_in, int dtype_out, void* d_workspace,
                            size_t workspace_bytes, void* stream) {
-    if (n_in < 0 || n_in > SC_N_MAX || n_out_cap < 0 || K < 1 || K > SC_K_MAX || C_in < 1 || C_out < 1) return SC_EINVAL;
+    if (n_map < 0 || n_map > SC_N_MAX || n_out_cap < 0 || K < 1 || K > SC_K_MAX || C_in < 1 || C_out < 1) return SC_EINVAL;
     if (d_weight == nullptr || d_kmap == nullptr || d_counts == nullptr) return SC_EINVAL;
-    if ((n_in > 0 && d_feat_in == nullptr) || (n_out_cap > 0 && d_feat_out == nullptr)) return SC_EINVAL;
+    if ((n_map > 0 && d_feat_in == nullptr) || (n_out_cap > 0 && d_feat_out == nullptr)) return SC_EINVAL;
     if (!aligned16(d_feat_in) || !aligned16(d_weight) || !aligned16(d_feat_out) || !aligned16(d_kmap) ||
         !aligned16(d_counts) || !aligned16(d_workspace))
         return SC_EINVAL;
     if (dtype_in != SC_F32 && dtype_in != SC_F16 && dtype_in != SC_BF16) return SC_EINVAL;
     if (dtype_out != SC_F32 && dtype_out != dtype_in) return SC_EINVAL;
-    const int64_t bound = sc_out_bound(n_in, K, stride, mode);
+    const int64_t bound = sc_out_bound(n_map, K, stride, mode);
     if (bound < 0) return SC_EINVAL;
-    if (kmap_bytes < sc_kmap_bytes(n_in, K, stride, mode)) return SC_ECAP;
+    if (kmap_bytes < sc_kmap_bytes(n_map, K, stride, mode)) return SC_ECAP;
+    // rows of the output: what the map build counted, or (inverse layers) the rows it was built from
+    const int64_t* n_out_ptr = mode == SC_INVERSE ? &d_counts->n_in : &d_counts->n_out;
     const KmapLayout L = kmap_layout(bound, K);
     int64_t tiles = (n_out_cap + TILE - 1) / TILE;
     if (tiles > L.tiles) tiles = L.tiles;
@@ -538,7 +540,7 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
     if (dtype_in == SC_F32) {
         if (C_out > 256) return SC_EINVAL;
         SC_LAUNCH(KID_CONV_F32, k_conv_f32, dim3((unsigned)tiles), dim3(256), 0, s, (const float*)d_feat_in,
-                  (const float*)d_weight, (float*)d_feat_out, gmask, nbr, L.K3, L.mw, C_in, C_out, d_counts,
+                  (const float*)d_weight, (float*)d_feat_out, gmask, nbr, L.K3, L.mw, C_in, C_out, n_out_ptr,
                   n_out_cap);
         return SC_OK;
     }
@@ -553,11 +555,11 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
         int rc;
         if (dtype_in == SC_F16)
             rc = launch_resident<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                         (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                         (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
                                          n_out_cap, &handled);
         else
             rc = launch_resident<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                          (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                          (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
                                           n_out_cap, &handled);
         if (handled || rc != SC_OK) return rc;
     }
@@ -569,21 +571,21 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_in, const void* d_we
         int rc;
         if (dtype_in == SC_F16)
             rc = launch_streamed<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                         (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                         (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
                                          n_out_cap, &handled);
         else
             rc = launch_streamed<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                          (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, d_counts,
+                                          (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
                                           n_out_cap, &handled);
         if (handled || rc != SC_OK) return rc;
     }
     if (dtype_in == SC_F16)
         SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_F16>, dim3((unsigned)tiles), dim3(256), 0, s,
                   (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
-                  C_in / 32, C_out / 16, d_counts, n_out_cap);
+                  C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
     else
         SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_BF16>, dim3((unsigned)tiles), dim3(256), 0, s,
                   (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
-                  C_in / 32, C_out / 16, d_counts, n_out_cap);
+                  C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
     return SC_OK;
 }

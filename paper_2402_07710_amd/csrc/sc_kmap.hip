@@ -316,11 +316,11 @@ k_counts_clear_pairs(sc_counts* counts) {
 
 // One wavefront per (tile, offset) line of the table: count the rows that have a neighbour.
 __global__ void __launch_bounds__(256)
-k_count_pairs(const int32_t* __restrict__ nbr, int K3, int64_t tiles_bound, sc_counts* counts) {
+k_count_pairs(const int32_t* __restrict__ nbr, int K3, int64_t tiles_bound, sc_counts* counts, int inverse) {
     __shared__ int32_t hist[343];
     for (int i = threadIdx.x; i < K3; i += blockDim.x) hist[i] = 0;
     __syncthreads();
-    int64_t tiles = (counts->n_out + TILE - 1) / TILE;
+    int64_t tiles = ((inverse ? counts->n_in : counts->n_out) + TILE - 1) / TILE;
     if (tiles > tiles_bound) tiles = tiles_bound;
     const int64_t items = tiles * K3;
     const int lane = threadIdx.x & 63;
@@ -383,10 +383,27 @@ k_write_starts(StartArg a, int count, int32_t* __restrict__ dst) {
     for (int i = threadIdx.x; i < count; i += blockDim.x) dst[i] = a.v[i];
 }
 
+// Inverse layer (Section III-E): the pairs of a strided map with input and output swapped.
+// One wavefront per coarse tile and offset line: row i of the fine set learns its coarse parent.
+__global__ void __launch_bounds__(256)
+k_transpose_scatter(const int32_t* __restrict__ nbr, int K3, const sc_counts* __restrict__ counts,
+                    int32_t* __restrict__ inv_nbr) {
+    const int lane = threadIdx.x & 63;
+    const int64_t tiles = (counts->n_out + TILE - 1) / TILE;
+    const int64_t items = tiles * K3;
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    for (int64_t it = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6); it < items; it += nwaves) {
+        const int64_t t = it / K3;
+        const int k = (int)(it - t * K3);
+        const int32_t i = nbr[it * TILE + lane];
+        if (i >= 0) inv_nbr[((int64_t)(i >> 6) * K3 + k) * TILE + (i & 63)] = (int32_t)(t * TILE + lane);
+    }
+}
+
 static bool kmap_args_ok(int64_t n, int K, int stride, int mode) {
     if (n < 0 || n > SC_N_MAX || K < 1 || K > SC_K_MAX) return false;
     if (mode == SC_SUBM) return stride == 1 && (K % 2) == 1;
-    if (mode == SC_STRIDED) return K == stride && K >= 2 && K <= 4;
+    if (mode == SC_STRIDED || mode == SC_INVERSE) return K == stride && K >= 2 && K <= 4;
     return false;
 }
 
@@ -484,6 +501,36 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     return SC_OK;
 }
 
+extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int stride, const sc_counts* d_counts,
+                                 void* d_kmap_inv, size_t kmap_inv_bytes, void* stream) {
+    if (!kmap_args_ok(n, K, stride, SC_STRIDED)) return SC_EINVAL;
+    if (d_kmap == nullptr || d_kmap_inv == nullptr || d_counts == nullptr || d_kmap == d_kmap_inv) return SC_EINVAL;
+    if (!aligned16(d_kmap) || !aligned16(d_kmap_inv) || !aligned16(d_counts)) return SC_EINVAL;
+    if (kmap_inv_bytes < sc_kmap_bytes(n, K, stride, SC_INVERSE)) return SC_ECAP;
+    hipStream_t s = (hipStream_t)stream;
+    const KmapLayout L = kmap_layout(n, K);          // same shape for both directions when K == stride
+    KmapHeader h{};
+    h.magic = KMAP_MAGIC; h.K = K; h.stride = stride; h.mode = SC_INVERSE;
+    h.n_in = n; h.n_out_bound = n; h.tiles = L.tiles; h.mw = L.mw;
+    SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap_inv, h);
+    if (n == 0) return SC_OK;
+    const int32_t* nbr = (const int32_t*)((const char*)d_kmap + L.off_nbr);
+    int32_t* inv_nbr = (int32_t*)((char*)d_kmap_inv + L.off_nbr);
+    uint32_t* inv_mask = (uint32_t*)((char*)d_kmap_inv + L.off_mask);
+    const int64_t nbr_vec = (int64_t)((L.bytes - L.off_nbr) / 16);
+    unsigned fb = (unsigned)((nbr_vec + 255) / 256);
+    if (fb > 4096) fb = 4096;
+    SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, (uint4*)nullptr, (uint64_t)0, (int4*)inv_nbr,
+              nbr_vec);
+    int64_t items = L.tiles * L.K3;
+    unsigned gb = (unsigned)((items + 3) / 4);
+    if (gb > 4096) gb = 4096;
+    SC_LAUNCH(KID_MISC, k_transpose_scatter, dim3(gb), dim3(256), 0, s, nbr, L.K3, d_counts, inv_nbr);
+    SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
+              (const int32_t*)inv_nbr, L.K3, L.mw, L.tiles, inv_mask);
+    return SC_OK;
+}
+
 extern "C" int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts, const void* d_kmap, int64_t n, int K,
                               int stride, int mode, void* stream) {
     if (d_counts == nullptr || h_counts == nullptr) return SC_EINVAL;
@@ -497,7 +544,8 @@ extern "C" int sc_counts_read(sc_counts* d_counts, sc_counts* h_counts, const vo
             unsigned gb = (unsigned)((items + 3) / 4);
             if (gb > 2048) gb = 2048;
             SC_LAUNCH(KID_COUNT_PAIRS, k_count_pairs, dim3(gb), dim3(256), 0, s,
-                      (const int32_t*)((const char*)d_kmap + L.off_nbr), L.K3, L.tiles, d_counts);
+                      (const int32_t*)((const char*)d_kmap + L.off_nbr), L.K3, L.tiles, d_counts,
+                      mode == SC_INVERSE ? 1 : 0);
         }
     }
     if (hipMemcpyAsync(h_counts, d_counts, sizeof(sc_counts), hipMemcpyDeviceToHost, s) != hipSuccess) return SC_EHIP;
@@ -522,7 +570,7 @@ extern "C" int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, 
     h_start.v[L.K3] = acc;
     if ((int64_t)acc != h_counts->n_pairs) return SC_EINVAL;
     SC_LAUNCH(KID_MISC, k_write_starts, dim3(1), dim3(256), 0, s, h_start, L.K3 + 1, d_offset_start);
-    const int64_t tiles = (h_counts->n_out + TILE - 1) / TILE;
+    const int64_t tiles = ((mode == SC_INVERSE ? h_counts->n_in : h_counts->n_out) + TILE - 1) / TILE;
     if (tiles > 0 && acc > 0)
         SC_LAUNCH(KID_EXPORT, k_export, dim3((unsigned)L.K3), dim3(1024), 0, s,
                   (const int32_t*)((const char*)d_kmap + L.off_nbr), L.K3, tiles, (const int32_t*)d_offset_start,

@@ -345,6 +345,28 @@ def check_expected_pairs_uniform(orc):
     assert abs(P - expect) < 5 * np.sqrt(expect - N), (P, expect)
 
 
+def check_inverse_is_adjoint(orc, rng, coords, s, C_f=3, C_c=4):
+    """The inverse layer built from a strided map is the adjoint of the strided layer when every
+    W[k] is transposed: <y, down(x; W)> = <up(y; W^T), x> for all x, y (Section III-E: the same
+    parent / offset relation, read in the other direction)."""
+    import oracle
+    n = len(coords)
+    km = orc.kmap(coords, s, s, "strided")
+    W = rng.standard_normal((s ** 3, C_f, C_c))
+    x = rng.standard_normal((n, C_f))
+    y = rng.standard_normal((km["n_out"], C_c))
+    down = orc.conv(x, W, km)
+    up = orc.conv(y, np.ascontiguousarray(W.transpose(0, 2, 1)), oracle.transpose_map(km))
+    assert up.shape == (n, C_f)
+    np.testing.assert_allclose(np.sum(y * down), np.sum(up * x), rtol=1e-10)
+    # and row by row: a fine row only hears from the cell that contains it
+    inv = oracle.transpose_map(km)
+    assert inv["offset_start"][-1] == n and np.array_equal(np.sort(inv["pair_out"]), np.arange(n))
+    cell = coords.copy()
+    cell[:, 1:] //= s
+    assert np.array_equal(km["out_coords"][inv["pair_in"]], cell[inv["pair_out"]])
+
+
 def run_all(orc, seed=0):
     """Every pin in one call (used on the real oracle and on each mutant)."""
     rng = np.random.default_rng(seed)
@@ -374,3 +396,4 @@ def run_all(orc, seed=0):
     check_alg2_formulation(orc, rng, c[:120], 3, 1, "subm")
     check_alg2_formulation(orc, rng, c[:120], 2, 2, "strided")
     check_expected_pairs_uniform(orc)
+    check_inverse_is_adjoint(orc, rng, c, 2)

@@ -254,6 +254,65 @@ def test_delta_weight_passthrough():
         assert np.array_equal(out, feat.astype(np.float64))
 
 
+# ---- map reuse and the inverse layer ------------------------------------------------------------
+def test_one_map_serves_several_layers():
+    """Layers over the same coordinates share one table and one map (the offset table is built
+    once per index set): two submanifold layers with different weights and channel counts."""
+    say("map reuse")
+    coords = synth.lidar_scene(3)[:20000]
+    n = len(coords)
+    d_coords = torch.from_numpy(coords).to(DEV)
+    buf = sc.LayerBuffers(n, 3, 1, "subm", 32, 64, "f16", device=DEV)
+    buf.hash_build(d_coords)
+    buf.kmap_build(d_coords)
+    ref_km = oracle.kmap(coords, 3, 1, "subm")
+    f1 = synth.features(n, 32, "f16", 1)
+    w1 = synth.weights(27, 32, 64, "f16", 1)
+    buf.conv_fwd(to_dev(f1, "f16"), to_dev(w1, "f16"))
+    out1 = buf.feat_out[:n].clone()
+    assert rel_err(out1.double().cpu().numpy(), oracle.conv(f1, w1, ref_km, threads=8)) <= TOL["f16"]
+    # second layer: the first layer's output as input, other weights, same map
+    f2 = out1.float().cpu().numpy()
+    w2 = synth.weights(27, 64, 64, "f16", 2)
+    out2 = torch.empty((n, 64), dtype=torch.float16, device=DEV)
+    ws = torch.empty(max(sc.sc_conv_workspace_bytes(3, 64, 64, "f16"), 16), dtype=torch.uint8, device=DEV)
+    sc.sc_conv_fwd(out1, to_dev(w2, "f16"), out2, buf.kmap, buf.counts, 3, 1, "subm", ws)
+    assert rel_err(out2.double().cpu().numpy(), oracle.conv(f2, w2, ref_km, threads=8)) <= TOL["f16"]
+
+
+@pytest.mark.parametrize("K,dtype,C_c,C_f", [(2, "f16", 64, 32), (2, "bf16", 128, 128), (3, "f16", 32, 32), (2, "f32", 8, 5)])
+def test_inverse_layer(K, dtype, C_c, C_f):
+    """Up-sampling: the strided layer's map transposed; every fine row gets parent . W[offset]."""
+    say(f"inverse K={K} {dtype}")
+    coords = synth.lidar_scene(4)[:30000]
+    n = len(coords)
+    d_coords = torch.from_numpy(coords).to(DEV)
+    buf = sc.LayerBuffers(n, K, K, "strided", 32, 32, "f16", device=DEV)
+    buf.hash_build(d_coords)
+    buf.kmap_build(d_coords)
+    h = buf.read_counts()
+    ref_km = oracle.kmap(coords, K, K, "strided")
+    ref_inv = oracle.transpose_map(ref_km)
+    n_c = int(h.n_out)
+    assert n_c == ref_km["n_out"]
+    kmap_inv = torch.empty(sc.sc_kmap_bytes(n, K, K, "inverse"), dtype=torch.uint8, device=DEV)
+    sc.sc_kmap_transpose(buf.kmap, n, K, K, buf.counts, kmap_inv)
+    h_inv = sc.sc_counts_read(buf.counts, kmap_inv, n, K, K, "inverse")
+    assert h_inv.n_pairs == n
+    pin, pout, ost = sc.sc_kmap_export(kmap_inv, n, K, K, "inverse", h_inv)
+    assert np.array_equal(ost.cpu().numpy(), ref_inv["offset_start"])
+    assert np.array_equal(pin.cpu().numpy(), ref_inv["pair_in"])
+    assert np.array_equal(pout.cpu().numpy(), ref_inv["pair_out"])
+    feat_c = synth.features(n_c, C_c, dtype, 7)
+    w = synth.weights(K ** 3, C_c, C_f, dtype, 7)
+    out = torch.empty((n, C_f), dtype=TDT[dtype], device=DEV)
+    ws = torch.empty(max(sc.sc_conv_workspace_bytes(K, C_c, C_f, dtype), 16), dtype=torch.uint8, device=DEV)
+    sc.sc_conv_fwd(to_dev(feat_c, dtype), to_dev(w, dtype), out, kmap_inv, buf.counts, K, K, "inverse", ws, n_map=n)
+    ref = oracle.conv(feat_c, w, ref_inv, threads=8)
+    err = rel_err(out.double().cpu().numpy(), ref)
+    assert err <= TOL[dtype], err
+
+
 # ---- the five named configurations at full size ----------------------------------------------
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "target64"])
 def test_named_config_full(name):

@@ -77,6 +77,13 @@ def test_alg2_formulation(orc, K, s, mode):
     pins.check_alg2_formulation(orc, np.random.default_rng(6), c, K, s, mode)
 
 
+@pytest.mark.parametrize("s", [2, 3])
+def test_inverse_is_adjoint(orc, s):
+    c = synth.uniform_cells(400, 10, seed=8)
+    c[:, 0] = np.arange(len(c)) % 2
+    pins.check_inverse_is_adjoint(orc, np.random.default_rng(8), c, s)
+
+
 def test_expected_pairs_uniform(orc):
     pins.check_expected_pairs_uniform(orc)
 
