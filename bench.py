@@ -54,6 +54,62 @@ def algorithmic_bytes(kernel: str, st: dict) -> float | None:
     return None
 
 
+def stage_bench(args, torch, sc, synth) -> int:
+    """Three chained layers on the cfg2 voxel set, the way an encoder stage runs them: two
+    submanifold 3x3x3 layers (32->32) that share ONE location table and ONE kernel map, then a
+    strided 2x2x2 layer (32->64) with its own map.  One step = all three; reports the amortised
+    time per layer."""
+    dev = "cuda:0"
+    cfg = synth.make_config("cfg2")
+    coords = cfg["coords"]
+    N = len(coords)
+    d_coords = torch.from_numpy(coords).to(dev)
+    d_feat = torch.from_numpy(cfg["feat"]).to(dev).half().contiguous()
+    w1 = torch.from_numpy(synth.weights(27, 32, 32, "f16", 1)).to(dev).half()
+    w2 = torch.from_numpy(synth.weights(27, 32, 32, "f16", 2)).to(dev).half()
+    w3 = torch.from_numpy(synth.weights(8, 32, 64, "f16", 3)).to(dev).half()
+    subm = sc.LayerBuffers(N, 3, 1, "subm", 32, 32, "f16", device=dev)
+    down = sc.LayerBuffers(N, 2, 2, "strided", 32, 64, "f16", device=dev)
+    mid = torch.empty((N, 32), dtype=torch.float16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        subm.hash_build(d_coords, stream)
+        subm.kmap_build(d_coords, stream)
+        subm.conv_fwd(d_feat, w1, stream)                                   # layer 1 -> subm.feat_out
+        sc.sc_conv_fwd(subm.feat_out, w2, mid, subm.kmap, subm.counts, 3, 1, "subm", subm.workspace, stream)
+        down.kmap_build(d_coords, stream)                                   # K == stride: no table needed
+        down.conv_fwd(mid, w3, stream)
+
+    step()
+    P1 = int(subm.read_counts().n_pairs)
+    hd = down.read_counts()
+    flops = 2.0 * (2 * P1 * 32 * 32 + int(hd.n_pairs) * 32 * 64)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    sc.sc_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    prof = sc.sc_profile_read()
+    sc.sc_profile_enable(False)
+    print(json.dumps({
+        "metric": "effective TFLOP/s over active MACs, three chained layers incl. their kernel maps",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "ms_per_layer_amortised": ms / 3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "cfg2-stage: subm 32->32, subm 32->32 (shared table and map), strided K=2 32->64",
+                   "N": N, "N_out_strided": int(hd.n_out), "P_subm": P1, "P_strided": int(hd.n_pairs)},
+        "kernels": {k: {"launches_per_step": l / args.steps, "avg_us": round(1e3 * t / l, 3)} for k, (l, t) in prof.items()},
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -83,6 +139,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     sc.load(build_if_missing=True)
 
+    if args.workload == "cfg2-stage":
+        return stage_bench(args, torch, sc, synth)
     cfg = synth.make_config(args.workload)
     coords, K, stride, mode = cfg["coords"], cfg["K"], cfg["stride"], cfg["mode"]
     C_in, C_out, dtype = cfg["C_in"], cfg["C_out"], cfg["dtype"]

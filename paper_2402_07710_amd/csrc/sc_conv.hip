@@ -22,6 +22,7 @@ namespace sc {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // W [K3][C_in][C_out] (16-bit elements) -> MFMA A-operand tiles of W[k]^T:
 // wp[((k*CB + cb)*KS + ks)*64 + lane] holds W[k][ks*32 + 8*(lane/16) + j][cb*16 + lane%16], j = 0..7
@@ -44,6 +45,14 @@ k_weight_pack(const uint16_t* __restrict__ w, uint4* __restrict__ wp, int K3, in
     for (int j = 0; j < 4; ++j)
         v[j] = (uint32_t)src[(int64_t)(2 * j) * C_out] | ((uint32_t)src[(int64_t)(2 * j + 1) * C_out] << 16);
     wp[t] = make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits until every
+// outstanding global load of the wavefront has returned (vmcnt(0)), which would drain the gathers
+// and weight fetches that were issued ahead on purpose; here only the wavefront's LDS operations
+// have to be complete before it arrives.
+__device__ inline void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 template <int DT>
@@ -171,138 +180,240 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     SC_MARK(5);
 }
 
-// ---- larger layers: W[k] streamed through LDS, one offset at a time ------------------------------
-// One wavefront per 64-row tile (four 16-row groups), four tiles per workgroup.  The workgroup
-// walks the offsets k that any of its groups needs, in lockstep.  While the matrix cores work on
-// offset k (weight tiles read from LDS, each applied to every group of the wavefront that has a
-// neighbour at k), the threads already fetch W[k'] of the next offset into registers, and as soon
-// as a 32-channel slice of the gathered rows has been used it is refilled with the rows of the
-// next offset; the offset-table lines are read two offsets ahead.  Accumulators (64 rows x C_out
-// per wavefront) never leave the registers.  KS = C_in/32, CB = C_out/16.
-template <int DT, int K3, int KS, int CB>
-__global__ void __launch_bounds__(256, 2)
-k_conv_stream(const uint16_t* __restrict__ feat, const uint4* __restrict__ wp, void* __restrict__ out, int out_f32,
-              const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
-              const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
+// A row of zeros that stands in for "no neighbour" in the streaming kernels: a lane without an
+// input row reads its operand from here, so every lane issues every load.  The compiler can then
+// count, at each use, exactly how many younger loads may still be in flight (s_waitcnt vmcnt(n));
+// a load that is skipped under a condition makes that count unknown and every wait becomes
+// vmcnt(0), which drains the loads that were issued ahead on purpose.
+__device__ __align__(256) uint4 g_zero_row[32];      // 512 bytes: a row of up to 256 16-bit channels
+
+// ---- mid-size layers: 16 rows per wavefront, W[k] streamed through LDS ----------------------------
+// When W does not fit in LDS as a whole but the layer is still small enough to be bound by
+// latency (64 channels on ~10^5 voxels), one wavefront per 16 rows keeps the most gathers in
+// flight: every wavefront reads all K3 of its offset-table lines first, then runs DEPTH-1 offsets
+// ahead with its feature gathers (a ring of DEPTH register slots), while the NW wavefronts of the
+// workgroup walk the offsets in lockstep and share W[k] through a double-buffered LDS tile.
+// Every offset is staged and every gather issued, also where the group has no neighbour (those
+// read the zero row): only the multiplies are skipped.
+template <int DT, int K3, int KS, int CB, int NW, int DEPTH>
+__global__ void __launch_bounds__(64 * NW)
+k_conv_rows16_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out,
+                     int out_f32, const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
+                     const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
-    static_assert((CB * KS) % 4 == 0, "a weight matrix is a whole number of 256-thread passes");
     constexpr int C_in = KS * 32, C_out = CB * 16;
     constexpr int WK = CB * KS * 64;                  // uint4 per packed W[k]
-    constexpr int WPT = WK / 256;                     // uint4 per thread per W[k]
-    extern __shared__ __align__(16) uint4 w_lds[];    // [2][WK]
-    __shared__ uint32_t bm_s;
+    static_assert(WK <= 64 * NW && (WK & (WK - 1)) == 0, "one uint4 of W[k] per thread");
+    __shared__ __align__(16) uint4 w_lds[2][WK];
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
-    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * 4 + wv;
+    const int64_t gidx = xcd_unit(blockIdx.x, gridDim.x) * NW + wv;          // 16-row group
+    const int64_t tile = gidx >> 2;
+    const int q = (int)(gidx & 3);
+    int64_t n_out = *n_out_ptr;
+    if (n_out > n_out_cap) n_out = n_out_cap;
+    const bool group_ok = tile * TILE + q * 16 < n_out;                       // uniform per wavefront
+
+    int32_t e[K3];
+    uint32_t m = 0;
+    if (group_ok) {
+        const int32_t* line = nbr + tile * (int64_t)(K3 * TILE) + q * 16 + r;
+#pragma unroll
+        for (int k = 0; k < K3; ++k) e[k] = line[k * TILE];
+        m = gmask[tile * 4 + q];
+    } else {
+#pragma unroll
+        for (int k = 0; k < K3; ++k) e[k] = -1;
+    }
+    m = __builtin_amdgcn_readfirstlane(m);
+    uint4 fb[DEPTH][KS];
+    auto gather = [&](int k, uint4 (&dst)[KS]) {
+        const uint4* frow =
+            (e[k] >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e[k] * C_in) : g_zero_row) + qq;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) dst[ks] = frow[ks * 4];
+    };
+#pragma unroll
+    for (int k = 0; k < DEPTH - 1 && k < K3; ++k) gather(k, fb[k % DEPTH]);
+
+    f32x4 acc[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // W[k] travels global -> registers (fetched three steps before use) -> LDS (two buffers,
+    // written one step before use).  With more threads than W[k] has uint4, two threads carry the
+    // same one: an unconditional load and store keep the fetch where it is written.
+    const int wslot = threadIdx.x & (WK - 1);
+    const uint4* wsrc = wp + wslot;
+    uint4 w_a = wsrc[0], w_b = wsrc[K3 > 1 ? WK : 0], w_c = wsrc[K3 > 2 ? 2 * WK : 0];
+    w_lds[0][wslot] = w_a;
+    w_a = w_b; w_b = w_c;
+    lds_barrier();
+#pragma unroll
+    for (int k = 0; k < K3; ++k) {
+        if (k + 3 < K3) w_c = wsrc[(int64_t)(k + 3) * WK];
+        if (k + DEPTH - 1 < K3) gather(k + DEPTH - 1, fb[(k + DEPTH - 1) % DEPTH]);
+        __builtin_amdgcn_sched_barrier(0);            // the fetches are issued here, not next to their use
+        if (m & (1u << k)) {
+            const uint4* wk = &w_lds[k & 1][lane];
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc[cb] = mfma16x16x32<DT>(wk[(cb * KS + ks) * 64], fb[k % DEPTH][ks], acc[cb]);
+        }
+        if (k + 1 < K3) {
+            w_lds[(k + 1) & 1][wslot] = w_a;
+            w_a = w_b; w_b = w_c;
+            lds_barrier();
+        }
+    }
+    const int64_t row = (gidx >> 2) * TILE + (gidx & 3) * 16 + r;
+    if (group_ok && row < n_out) {
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) store_acc<DT>(out, out_f32, row, C_out, cb * 16 + qq * 4, acc[cb]);
+    }
+}
+
+// ---- larger layers: W[k] streamed through LDS, one offset at a time ------------------------------
+// One wavefront per 64-row tile (four 16-row groups), NWV tiles per workgroup.  The workgroup
+// walks the K3 offsets in lockstep; W[k] reaches the matrix cores through a double-buffered LDS
+// tile, each weight operand read once and applied to every group of the wavefront that has a
+// neighbour at k.  Everything else is arranged so that loads stay in flight across steps:
+//  * the tile's offset-table lines are copied to LDS once, up front, so the loop reads neighbour
+//    indices through the LDS counter and never has to wait on the vector-memory counter for them
+//    (that counter retires in order: waiting for a young index load would drain every older
+//    gather and weight fetch with it);
+//  * gathered rows live in a ring of D register slots: as soon as a 32-channel slice of slot
+//    k % D has been used it is refilled with the rows of offset k + D;
+//  * W[k + D] is fetched into registers at the top of step k and stored to LDS at the end of step
+//    k + D - 1;
+//  * every load is issued by every lane (rows without a neighbour read the zero row), only the
+//    multiplies are skipped, so all waits are exact counts.
+// Accumulators (64 rows x C_out per wavefront) never leave the registers.  KS = C_in/32,
+// CB = C_out/16.
+template <int DT, int K3, int KS, int CB, int NWV, int D>
+__global__ void __launch_bounds__(64 * NWV, 2)
+k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
+              const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
+              const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
+    static_assert(K3 <= 32, "one mask word per group");
+    constexpr int NTH = 64 * NWV;
+    constexpr int C_in = KS * 32, C_out = CB * 16;
+    constexpr int WK = CB * KS * 64;                  // uint4 per packed W[k]
+    static_assert(WK % NTH == 0, "a weight matrix is a whole number of passes of the workgroup");
+    constexpr int WPT = WK / NTH;                     // uint4 per thread per W[k]
+    constexpr int CBG = CB < 4 ? CB : 4;              // weight operands held at a time
+    static_assert(CB % CBG == 0, "whole operand batches");
+    extern __shared__ __align__(16) uint4 smem[];     // w_lds[2][WK] | e_lds[NWV][K3][64]
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int r = lane & 15, qq = lane >> 4;
+    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NWV + wv;
+    uint4* w_lds = smem;
+    int32_t* e_lds = reinterpret_cast<int32_t*>(smem + 2 * WK) + wv * (K3 * TILE);
     SC_MARK(0);
     int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
     const bool tile_ok = tile * TILE < n_out;
-    if (threadIdx.x == 0) bm_s = 0u;
 
-    uint32_t mg0 = 0u, mg1 = 0u, mg2 = 0u, mg3 = 0u;
-    if (tile_ok) {
-        mg0 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 0]);
-        mg1 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 1]);
-        mg2 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 2]);
-        mg3 = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + 3]);
+    uint32_t mg[4] = {0u, 0u, 0u, 0u};
+    {   // the tile's offset-table lines -> LDS (read back below by other lanes of this wavefront)
+        int32_t v[K3];
+        if (tile_ok) {
+            const int32_t* line = nbr + tile * (int64_t)(K3 * TILE) + lane;
+#pragma unroll
+            for (int k = 0; k < K3; ++k) v[k] = line[k * TILE];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) mg[g] = gmask[tile * 4 + g];
+        } else {
+#pragma unroll
+            for (int k = 0; k < K3; ++k) v[k] = -1;
+        }
+#pragma unroll
+        for (int k = 0; k < K3; ++k) e_lds[k * TILE + lane] = v[k];
     }
-    const uint32_t many = mg0 | mg1 | mg2 | mg3;
-    __syncthreads();
-    if (lane == 0 && many) atomicOr(&bm_s, many);
-    __syncthreads();
-    uint32_t todo = bm_s;                             // offsets some group of the workgroup needs
+#pragma unroll
+    for (int g = 0; g < 4; ++g) mg[g] = __builtin_amdgcn_readfirstlane(mg[g]);
     SC_MARK(1);
 
-    // the tile's offset-table line of offset k: lane (g, r) <- row 16g + r ... one value per group
-    const int32_t* my_nbr = nbr + tile * (int64_t)(K3 * TILE) + r;
-    auto next_offset = [&]() -> int {
-        if (!todo) return -1;
-        const int k = __builtin_ctz(todo);
-        todo &= todo - 1;
-        return k;
-    };
-    auto has = [&](int g, int k) -> bool {
-        const uint32_t m = g == 0 ? mg0 : g == 1 ? mg1 : g == 2 ? mg2 : mg3;
-        return (m >> k) & 1u;
-    };
+    const u32x4* wsrc = reinterpret_cast<const u32x4*>(wp) + threadIdx.x;
+    u32x4 wr[D][WPT];
+#pragma unroll
+    for (int j = 0; j < D && j < K3; ++j)
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) wr[j][i] = wsrc[(int64_t)j * WK + i * NTH];
 
+    auto rowptr = [&](int32_t e) -> const uint4* {
+        return (e >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e * C_in) : g_zero_row) + qq;
+    };
+    uint4 fb[D][4][KS];
+#pragma unroll
+    for (int j = 0; j < D && j < K3; ++j) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const uint4* frow = rowptr(e_lds[j * TILE + g * 16 + r]);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) fb[j][g][ks] = frow[ks * 4];
+        }
+    }
     f32x4 acc[4][CB];
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) acc[g][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    uint4 fb[4][KS];
-    int32_t e_nxt[4] = {-1, -1, -1, -1};
-
-    int kc = next_offset(), kn = next_offset();
-    if (kc >= 0) {
-        uint4 wn[WPT];
-        int32_t e_cur[4];
-        {
-            const uint4* src = wp + (int64_t)kc * WK + threadIdx.x;
 #pragma unroll
-            for (int i = 0; i < WPT; ++i) wn[i] = src[i * 256];
-        }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) e_cur[g] = (tile_ok && has(g, kc)) ? my_nbr[kc * TILE + g * 16] : -1;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) e_nxt[g] = (tile_ok && kn >= 0 && has(g, kn)) ? my_nbr[kn * TILE + g * 16] : -1;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const uint4* frow = reinterpret_cast<const uint4*>(feat + (int64_t)(e_cur[g] < 0 ? 0 : e_cur[g]) * C_in) + qq;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) fb[g][ks] = e_cur[g] >= 0 ? frow[ks * 4] : make_uint4(0, 0, 0, 0);
-        }
-        uint4* dst = w_lds + threadIdx.x;
-#pragma unroll
-        for (int i = 0; i < WPT; ++i) dst[i * 256] = wn[i];
-    }
-    __syncthreads();
+    for (int i = 0; i < WPT; ++i) reinterpret_cast<u32x4*>(w_lds)[threadIdx.x + i * NTH] = wr[0][i];
+    lds_barrier();
     SC_MARK(2);
-    int buf = 0;
-    while (kc >= 0) {
-        const int knn = next_offset();
-        uint4 wn[WPT];
-        {
-            const uint4* src = wp + (int64_t)(kn >= 0 ? kn : kc) * WK + threadIdx.x;   // last step: a harmless re-read
+
 #pragma unroll
-            for (int i = 0; i < WPT; ++i) wn[i] = src[i * 256];
+    for (int k = 0; k < K3; ++k) {
+        const bool more = k + D < K3;
+#ifdef SC_TRACE
+        if (k == 1) SC_MARK(6);
+        if (k == 9) SC_MARK(7);
+        if (k == 17) SC_MARK(8);
+        if (k == 25) SC_MARK(9);
+#endif
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < WPT; ++i) wr[k % D][i] = wsrc[(int64_t)(k + D) * WK + i * NTH];
         }
-        int32_t e_nn[4];
+        int32_t e4[4] = {-1, -1, -1, -1};
+        if (more) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) e_nn[g] = (tile_ok && knn >= 0 && has(g, knn)) ? my_nbr[knn * TILE + g * 16] : -1;
-        const uint4* wk = w_lds + buf * WK + lane;
+            for (int g = 0; g < 4; ++g) e4[g] = e_lds[(k + D) * TILE + g * 16 + r];
+        }
+        __builtin_amdgcn_sched_barrier(0);            // the fetches are issued here, not next to their use
+        const uint4* wk = w_lds + (k & 1) * WK + lane;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const uint4 a = wk[(cb * KS + ks) * 64];
+            for (int c0 = 0; c0 < CB; c0 += CBG) {
+                uint4 a[CBG];
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    if (has(g, kc)) acc[g][cb] = mfma16x16x32<DT>(a, fb[g][ks], acc[g][cb]);
-            }
-            if (kn >= 0) {          // this slice is free: refill it with the next offset's rows
+                for (int c = 0; c < CBG; ++c) a[c] = wk[((c0 + c) * KS + ks) * 64];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    if (has(g, kn)) {
-                        const uint4* frow =
-                            reinterpret_cast<const uint4*>(feat + (int64_t)(e_nxt[g] < 0 ? 0 : e_nxt[g]) * C_in) + qq;
-                        fb[g][ks] = e_nxt[g] >= 0 ? frow[ks * 4] : make_uint4(0, 0, 0, 0);
+                    if ((mg[g] >> k) & 1u) {
+#pragma unroll
+                        for (int c = 0; c < CBG; ++c)
+                            acc[g][c0 + c] = mfma16x16x32<DT>(a[c], fb[k % D][g][ks], acc[g][c0 + c]);
                     }
                 }
             }
-        }
-        {
-            uint4* dst = w_lds + (buf ^ 1) * WK + threadIdx.x;
+            if (more) {             // this slice is free: refill it with the rows of offset k + D
 #pragma unroll
-            for (int i = 0; i < WPT; ++i) dst[i * 256] = wn[i];
+                for (int g = 0; g < 4; ++g) fb[k % D][g][ks] = rowptr(e4[g])[ks * 4];
+            }
         }
-        __syncthreads();
+        if (k + 1 < K3) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) e_nxt[g] = e_nn[g];
-        kc = kn; kn = knn; buf ^= 1;
+            for (int i = 0; i < WPT; ++i)
+                reinterpret_cast<u32x4*>(w_lds)[((k + 1) & 1) * WK + threadIdx.x + i * NTH] = wr[(k + 1) % D][i];
+            lds_barrier();
+        }
     }
     SC_MARK(3);
     if (tile_ok) {
@@ -463,19 +574,29 @@ static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream
     return SC_OK;
 }
 
-template <int DT, int K3, int KS, int CB>
+template <int DT, int K3, int KS, int CB, int NWV, int D>
 static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_stream<DT, K3, KS, CB>;
-    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4);
+    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D>;
+    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (size_t)NWV * K3 * TILE * sizeof(int32_t);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return SC_EHIP;
         attr_set = true;
     }
-    SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + 3) / 4)), dim3(256), lds, s, feat, wp, out, out_f32, gmask,
-              nbr, counts, n_out_cap);
+    SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + NWV - 1) / NWV)), dim3(64 * NWV), lds, s, feat, wp, out, out_f32,
+              gmask, nbr, counts, n_out_cap);
+    return SC_OK;
+}
+
+template <int DT, int K3, int KS, int CB, int NW, int DEPTH>
+static int launch_rows16_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out,
+                                int out_f32, const uint32_t* gmask, const int32_t* nbr, const int64_t* counts,
+                                int64_t n_out_cap) {
+    const int64_t groups = tiles * 4;
+    SC_LAUNCH(KID_CONV_MFMA, (k_conv_rows16_stream<DT, K3, KS, CB, NW, DEPTH>), dim3(xcd_grid((groups + NW - 1) / NW)),
+              dim3(64 * NW), 0, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
     return SC_OK;
 }
 
@@ -485,14 +606,25 @@ static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream
                            const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
                            const int64_t* counts, int64_t n_out_cap, bool* handled) {
     *handled = true;
-#define SC_STREAM(K3V, KSV, CBV) \
-    return launch_stream<DT, K3V, KSV, CBV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
-    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4);
-    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8);
-    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4);
-    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8);
-    if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8);
-    if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8);
+#define SC_STREAM(K3V, KSV, CBV, NWV, DV) \
+    return launch_stream<DT, K3V, KSV, CBV, NWV, DV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
+    static const int v64 = getenv("SC_CONV64") ? atoi(getenv("SC_CONV64")) : 1;
+    if (K3 == 27 && C_in == 64 && C_out == 64 && tiles <= 8192) {       // latency-bound sizes
+        if (v64 == 1) return launch_rows16_stream<DT, 27, 2, 4, 16, 8>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
+        if (v64 == 2) return launch_rows16_stream<DT, 27, 2, 4, 16, 12>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
+        if (v64 == 3) return launch_rows16_stream<DT, 27, 2, 4, 8, 8>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
+        if (v64 == 4) return launch_rows16_stream<DT, 27, 2, 4, 8, 12>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
+    }
+    if (K3 == 27 && C_in == 64 && C_out == 64) {
+        if (v64 == 5) SC_STREAM(27, 2, 4, 4, 2);
+        if (v64 == 6) SC_STREAM(27, 2, 4, 4, 4);
+        SC_STREAM(27, 2, 4, 4, 3);
+    }
+    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1);
+    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3);
+    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2);
+    if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2);
+    if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1);
 #undef SC_STREAM
     *handled = false;
     return SC_OK;
