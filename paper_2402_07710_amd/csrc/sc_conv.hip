@@ -187,94 +187,6 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
 // vmcnt(0), which drains the loads that were issued ahead on purpose.
 __device__ __align__(256) uint4 g_zero_row[32];      // 512 bytes: a row of up to 256 16-bit channels
 
-// ---- mid-size layers: 16 rows per wavefront, W[k] streamed through LDS ----------------------------
-// When W does not fit in LDS as a whole but the layer is still small enough to be bound by
-// latency (64 channels on ~10^5 voxels), one wavefront per 16 rows keeps the most gathers in
-// flight: every wavefront reads all K3 of its offset-table lines first, then runs DEPTH-1 offsets
-// ahead with its feature gathers (a ring of DEPTH register slots), while the NW wavefronts of the
-// workgroup walk the offsets in lockstep and share W[k] through a double-buffered LDS tile.
-// Every offset is staged and every gather issued, also where the group has no neighbour (those
-// read the zero row): only the multiplies are skipped.
-template <int DT, int K3, int KS, int CB, int NW, int DEPTH>
-__global__ void __launch_bounds__(64 * NW)
-k_conv_rows16_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out,
-                     int out_f32, const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
-                     const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
-    static_assert(K3 <= 32, "one mask word per group");
-    constexpr int C_in = KS * 32, C_out = CB * 16;
-    constexpr int WK = CB * KS * 64;                  // uint4 per packed W[k]
-    static_assert(WK <= 64 * NW && (WK & (WK - 1)) == 0, "one uint4 of W[k] per thread");
-    __shared__ __align__(16) uint4 w_lds[2][WK];
-
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int r = lane & 15, qq = lane >> 4;
-    const int64_t gidx = xcd_unit(blockIdx.x, gridDim.x) * NW + wv;          // 16-row group
-    const int64_t tile = gidx >> 2;
-    const int q = (int)(gidx & 3);
-    int64_t n_out = *n_out_ptr;
-    if (n_out > n_out_cap) n_out = n_out_cap;
-    const bool group_ok = tile * TILE + q * 16 < n_out;                       // uniform per wavefront
-
-    int32_t e[K3];
-    uint32_t m = 0;
-    if (group_ok) {
-        const int32_t* line = nbr + tile * (int64_t)(K3 * TILE) + q * 16 + r;
-#pragma unroll
-        for (int k = 0; k < K3; ++k) e[k] = line[k * TILE];
-        m = gmask[tile * 4 + q];
-    } else {
-#pragma unroll
-        for (int k = 0; k < K3; ++k) e[k] = -1;
-    }
-    m = __builtin_amdgcn_readfirstlane(m);
-    uint4 fb[DEPTH][KS];
-    auto gather = [&](int k, uint4 (&dst)[KS]) {
-        const uint4* frow =
-            (e[k] >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e[k] * C_in) : g_zero_row) + qq;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) dst[ks] = frow[ks * 4];
-    };
-#pragma unroll
-    for (int k = 0; k < DEPTH - 1 && k < K3; ++k) gather(k, fb[k % DEPTH]);
-
-    f32x4 acc[CB];
-#pragma unroll
-    for (int cb = 0; cb < CB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // W[k] travels global -> registers (fetched three steps before use) -> LDS (two buffers,
-    // written one step before use).  With more threads than W[k] has uint4, two threads carry the
-    // same one: an unconditional load and store keep the fetch where it is written.
-    const int wslot = threadIdx.x & (WK - 1);
-    const uint4* wsrc = wp + wslot;
-    uint4 w_a = wsrc[0], w_b = wsrc[K3 > 1 ? WK : 0], w_c = wsrc[K3 > 2 ? 2 * WK : 0];
-    w_lds[0][wslot] = w_a;
-    w_a = w_b; w_b = w_c;
-    lds_barrier();
-#pragma unroll
-    for (int k = 0; k < K3; ++k) {
-        if (k + 3 < K3) w_c = wsrc[(int64_t)(k + 3) * WK];
-        if (k + DEPTH - 1 < K3) gather(k + DEPTH - 1, fb[(k + DEPTH - 1) % DEPTH]);
-        __builtin_amdgcn_sched_barrier(0);            // the fetches are issued here, not next to their use
-        if (m & (1u << k)) {
-            const uint4* wk = &w_lds[k & 1][lane];
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc[cb] = mfma16x16x32<DT>(wk[(cb * KS + ks) * 64], fb[k % DEPTH][ks], acc[cb]);
-        }
-        if (k + 1 < K3) {
-            w_lds[(k + 1) & 1][wslot] = w_a;
-            w_a = w_b; w_b = w_c;
-            lds_barrier();
-        }
-    }
-    const int64_t row = (gidx >> 2) * TILE + (gidx & 3) * 16 + r;
-    if (group_ok && row < n_out) {
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) store_acc<DT>(out, out_f32, row, C_out, cb * 16 + qq * 4, acc[cb]);
-    }
-}
-
 // ---- larger layers: W[k] streamed through LDS, one offset at a time ------------------------------
 // One wavefront per 64-row tile (four 16-row groups), NWV tiles per workgroup.  The workgroup
 // walks the K3 offsets in lockstep; W[k] reaches the matrix cores through a double-buffered LDS
@@ -370,12 +282,6 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
 #pragma unroll
     for (int k = 0; k < K3; ++k) {
         const bool more = k + D < K3;
-#ifdef SC_TRACE
-        if (k == 1) SC_MARK(6);
-        if (k == 9) SC_MARK(7);
-        if (k == 17) SC_MARK(8);
-        if (k == 25) SC_MARK(9);
-#endif
         if (more) {
 #pragma unroll
             for (int i = 0; i < WPT; ++i) wr[k % D][i] = wsrc[(int64_t)(k + D) * WK + i * NTH];
@@ -590,16 +496,6 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
     return SC_OK;
 }
 
-template <int DT, int K3, int KS, int CB, int NW, int DEPTH>
-static int launch_rows16_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out,
-                                int out_f32, const uint32_t* gmask, const int32_t* nbr, const int64_t* counts,
-                                int64_t n_out_cap) {
-    const int64_t groups = tiles * 4;
-    SC_LAUNCH(KID_CONV_MFMA, (k_conv_rows16_stream<DT, K3, KS, CB, NW, DEPTH>), dim3(xcd_grid((groups + NW - 1) / NW)),
-              dim3(64 * NW), 0, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
-    return SC_OK;
-}
-
 // Shapes with a streaming kernel.
 template <int DT>
 static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
@@ -608,18 +504,7 @@ static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream
     *handled = true;
 #define SC_STREAM(K3V, KSV, CBV, NWV, DV) \
     return launch_stream<DT, K3V, KSV, CBV, NWV, DV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
-    static const int v64 = getenv("SC_CONV64") ? atoi(getenv("SC_CONV64")) : 1;
-    if (K3 == 27 && C_in == 64 && C_out == 64 && tiles <= 8192) {       // latency-bound sizes
-        if (v64 == 1) return launch_rows16_stream<DT, 27, 2, 4, 16, 8>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
-        if (v64 == 2) return launch_rows16_stream<DT, 27, 2, 4, 16, 12>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
-        if (v64 == 3) return launch_rows16_stream<DT, 27, 2, 4, 8, 8>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
-        if (v64 == 4) return launch_rows16_stream<DT, 27, 2, 4, 8, 12>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
-    }
-    if (K3 == 27 && C_in == 64 && C_out == 64) {
-        if (v64 == 5) SC_STREAM(27, 2, 4, 4, 2);
-        if (v64 == 6) SC_STREAM(27, 2, 4, 4, 4);
-        SC_STREAM(27, 2, 4, 4, 3);
-    }
+    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4, 4, 3);
     if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1);
     if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3);
     if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2);
