@@ -40,6 +40,11 @@ def algorithmic_bytes(kernel: str, st: dict) -> float | None:
     if kernel == "k_kmap_subm":
         # coords, one 8-byte key per neighbour probe, 4 bytes per hit, one 4-byte table cell per (row, offset)
         return N * 16 + N * (K3 - 1) * 8 + (P - N) * 4 + N * K3 * 4
+    if kernel == "k_grid_insert":
+        return N * (16 + 8 + 8)                           # coords, one 8-byte cell exchanged (read + write)
+    if kernel == "k_kmap_subm_grid":
+        # coords, one 8-byte cell per neighbour probe, one 4-byte table cell per (row, offset)
+        return N * 16 + N * (K3 - 1) * 8 + N * K3 * 4
     if kernel in ("k_conv_mfma", "k_conv_f32"):
         # features in once, features out once, weights once, 8 bytes of map per pair
         return N * C_in * e + N_out * C_out * e + K3 * C_in * C_out * e + P * 8
@@ -116,6 +121,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--table", choices=["hash", "grid"], default="hash",
+                    help="location table: the open-addressing hash table (default, what the metric is quoted on) or "
+                         "the dense array over the workload's voxel box (submanifold workloads only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="off",
                     help="replay the step from a captured HIP graph instead of launching eagerly "
@@ -149,7 +157,11 @@ def main() -> int:
     d_coords = torch.from_numpy(coords).to(dev)
     d_feat = torch.from_numpy(cfg["feat"]).to(dev).to(tdt).contiguous()
     d_w = torch.from_numpy(cfg["weight"]).to(dev).to(tdt).contiguous()
-    buf = sc.LayerBuffers(N, K, stride, mode, C_in, C_out, dtype, device=dev)
+    if args.table == "grid" and mode != "subm":
+        print("bench.py: --table grid applies to submanifold workloads only", file=sys.stderr)
+        return 2
+    buf = sc.LayerBuffers(N, K, stride, mode, C_in, C_out, dtype, device=dev,
+                          grid_dims=cfg["box"] if args.table == "grid" else None)
     stream = torch.cuda.current_stream()
 
     def step():
@@ -257,7 +269,7 @@ def main() -> int:
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload, {}).get(dominant)
+        traffic = json.load(open(tpath)).get(args.workload if args.table == "hash" else args.workload + "-grid", {}).get(dominant)
     if dominant in ("k_conv_mfma", "k_conv_f32"):
         # the contraction: flops of the pairs that exist against the matrix-core (or fp32 ALU) peak
         peak = PEAK_MFMA_TFLOPS if dominant == "k_conv_mfma" else PEAK_FP32_TFLOPS
@@ -287,7 +299,7 @@ def main() -> int:
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "mode": mode, "K": K, "stride": stride, "C_in": C_in,
+        "config": {"workload": args.workload, "table": args.table, "mode": mode, "K": K, "stride": stride, "C_in": C_in,
                    "C_out": C_out, "N": N, "N_out": N_out, "P": P, "pairs_per_voxel": P / max(N, 1)},
         "launch": "hip graph replay" if graph is not None else "eager", "ms_per_step_eager": ms_per_step_eager,
         "phases_ms": phases, "kernels": per_kernel, "roofline": roofline,

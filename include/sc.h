@@ -79,7 +79,8 @@ typedef struct sc_counts {
 /* ---- location table (Section III-C.1; the paper offers a dense array or a hash table, this
  * library uses an open-addressing hash table keyed on the packed 64-bit (b,x,y,z)) ---------- */
 
-/* Bytes of the table for n keys (capacity = power of two >= 2n, so the load factor is <= 1/2). */
+/* Bytes of the table for n keys: 16 bytes per slot, capacity = power of two >= 4n and >= 1024
+ * slots, so the load factor stays <= 1/4. */
 size_t sc_hash_bytes(int64_t n);
 
 /* Build the table coordinate -> row index over d_coords [n][4] (b,x,y,z).  Also resets
@@ -88,6 +89,39 @@ size_t sc_hash_bytes(int64_t n);
 int sc_hash_build(const int32_t* d_coords, int64_t n,
                   void* d_table, size_t table_bytes,
                   sc_counts* d_counts, void* stream);
+
+/* ---- dense location table (Section III-C.1 offers both forms: a "large array" indexed by the
+ * linearised coordinate, eq. 6, which the paper prefers when the domain is confined, or a hash
+ * table; this is the array, as an alternative to sc_hash_build for submanifold layers) -------
+ *
+ * The table covers the box 0 <= b < B, 0 <= x < X, 0 <= y < Y, 0 <= z < Z with one 8-byte cell
+ * per site (z runs fastest).  A cell holds a row index and the `epoch` of the build that wrote
+ * it; look-ups only accept cells of the epoch they are given.  The caller clears the array once
+ * (sc_grid_clear) and then passes a fresh epoch >= 1 to every sc_grid_build - any value it has
+ * not used on this array since the last clear, e.g. a counter - so a build costs one scatter of
+ * n cells: no fill before it, no clean-up after it.  Clear again before the counter wraps. */
+
+#define SC_GRID_CELLS_MAX 8589934592LL   /* 2^33 sites = 64 GiB of cells */
+
+/* Bytes of the array for the box, 0 if a side is < 1 or > SC_COORD_MAX + 1 or the box has more
+ * than SC_GRID_CELLS_MAX sites. */
+size_t sc_grid_bytes(int32_t B, int32_t X, int32_t Y, int32_t Z);
+
+/* Zero the array (all cells unoccupied for every epoch >= 1). */
+int sc_grid_clear(void* d_grid, size_t grid_bytes, int32_t B, int32_t X, int32_t Y, int32_t Z, void* stream);
+
+/* Scatter the n rows of d_coords [n][4] into the array under `epoch` (plain stores, as in the
+ * paper's table kernel).  Also resets *d_counts (n_in = n, everything else 0).  Nothing is
+ * checked here: a coordinate outside the box, or two rows with one coordinate, are found by
+ * sc_kmap_build_grid, which latches SC_ERANGE / SC_EDUP into d_counts->status.  Returns
+ * SC_EINVAL for epoch 0. */
+int sc_grid_build(const int32_t* d_coords, int64_t n,
+                  void* d_grid, size_t grid_bytes, int32_t B, int32_t X, int32_t Y, int32_t Z,
+                  uint32_t epoch, sc_counts* d_counts, void* stream);
+
+/* d_rows[i] = row index of d_query[i] in the build of `epoch`, or -1. */
+int sc_grid_lookup(const void* d_grid, int32_t B, int32_t X, int32_t Y, int32_t Z, uint32_t epoch,
+                   const int32_t* d_query, int64_t n_query, int32_t* d_rows, void* stream);
 
 /* ---- offset table / kernel map (Section III-C.2 for submanifold layers: probe the K^3
  * neighbours of every active site in the location table; Section III-B eq. 1-5 and
@@ -127,6 +161,16 @@ int sc_kmap_build(const int32_t* d_coords, int64_t n,
                   void* d_kmap, size_t kmap_bytes,
                   void* d_scratch, size_t scratch_bytes,
                   sc_counts* d_counts, void* stream);
+
+/* The submanifold kernel map (mode SC_SUBM, stride 1, K odd) from a dense location table built by
+ * sc_grid_build(d_coords, n, ..., epoch): same blob, same meaning of every other argument as in
+ * sc_kmap_build; needs no scratch buffer.  Every row reads its own cell: a row outside the box
+ * latches SC_ERANGE, a cell that names another row (two rows, one coordinate) latches SC_EDUP. */
+int sc_kmap_build_grid(const int32_t* d_coords, int64_t n,
+                       const void* d_grid, size_t grid_bytes, int32_t B, int32_t X, int32_t Y, int32_t Z,
+                       uint32_t epoch, int K,
+                       void* d_kmap, size_t kmap_bytes,
+                       sc_counts* d_counts, void* stream);
 
 /* Inverse (up-sampling) layer, Section III-E: every row of the fine set finds its parent in the
  * coarse set and its place in the kernel, and receives parent_features . W[place].  The pairs are

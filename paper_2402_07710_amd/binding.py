@@ -27,7 +27,8 @@ TORCH_DTYPES = {SC_F32: torch.float32, SC_F16: torch.float16, SC_BF16: torch.bfl
 # every symbol include/sc.h declares
 SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
-           "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read"]
+           "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
+           "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid"]
 
 
 class ScCounts(ctypes.Structure):
@@ -79,6 +80,11 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_strerror": (ctypes.c_char_p, [i32]),
         "sc_profile_enable": (i32, [i32]),
         "sc_profile_read": (i32, [ctypes.POINTER(ScProfileEntry), i32]),
+        "sc_grid_bytes": (sz, [i32, i32, i32, i32]),
+        "sc_grid_clear": (i32, [vp, sz, i32, i32, i32, i32, vp]),
+        "sc_grid_build": (i32, [vp, i64, vp, sz, i32, i32, i32, i32, ctypes.c_uint32, vp, vp]),
+        "sc_grid_lookup": (i32, [vp, i32, i32, i32, i32, ctypes.c_uint32, vp, i64, vp, vp]),
+        "sc_kmap_build_grid": (i32, [vp, i64, vp, sz, i32, i32, i32, i32, ctypes.c_uint32, i32, vp, sz, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -153,6 +159,31 @@ def sc_kmap_build(coords, table, K, stride, mode, out_coords, kmap, scratch, cou
                                 _ptr(counts), _stream(stream)), "sc_kmap_build")
 
 
+def sc_grid_bytes(B: int, X: int, Y: int, Z: int) -> int:
+    return load().sc_grid_bytes(B, X, Y, Z)
+
+
+def sc_grid_clear(grid, dims, stream=None):
+    _check(load().sc_grid_clear(_ptr(grid), grid.numel() * grid.element_size(), *dims, _stream(stream)), "sc_grid_clear")
+
+
+def sc_grid_build(coords, grid, dims, epoch, counts, stream=None):
+    """coords int32 [n,4] (device), grid uint8 [>= sc_grid_bytes(*dims)], dims = (B, X, Y, Z)."""
+    _check(load().sc_grid_build(_ptr(coords), coords.shape[0], _ptr(grid), grid.numel() * grid.element_size(), *dims,
+                                epoch, _ptr(counts), _stream(stream)), "sc_grid_build")
+
+
+def sc_grid_lookup(grid, dims, epoch, query, rows, stream=None):
+    _check(load().sc_grid_lookup(_ptr(grid), *dims, epoch, _ptr(query), query.shape[0], _ptr(rows), _stream(stream)),
+           "sc_grid_lookup")
+
+
+def sc_kmap_build_grid(coords, grid, dims, epoch, K, kmap, counts, stream=None):
+    _check(load().sc_kmap_build_grid(_ptr(coords), coords.shape[0], _ptr(grid), grid.numel() * grid.element_size(),
+                                     *dims, epoch, K, _ptr(kmap), kmap.numel() * kmap.element_size(), _ptr(counts),
+                                     _stream(stream)), "sc_kmap_build_grid")
+
+
 def sc_kmap_transpose(kmap, n, K, stride, counts, kmap_inv, stream=None):
     _check(load().sc_kmap_transpose(_ptr(kmap), n, K, stride, _ptr(counts), _ptr(kmap_inv),
                                     kmap_inv.numel() * kmap_inv.element_size(), _stream(stream)), "sc_kmap_transpose")
@@ -213,7 +244,9 @@ class LayerBuffers:
     in order.  Holds no arithmetic: it sizes buffers with the library's own *_bytes calls."""
 
     def __init__(self, n: int, K: int, stride: int, mode, C_in: int, C_out: int, dtype, out_dtype=None,
-                 device="cuda:0"):
+                 device="cuda:0", grid_dims=None):
+        """grid_dims = (B, X, Y, Z): use the dense location table over that box instead of the hash
+        table (submanifold layers only)."""
         self.n, self.K, self.stride, self.mode = n, K, stride, MODES[mode]
         self.C_in, self.C_out = C_in, C_out
         self.dtype = TORCH_DTYPES[DTYPES[dtype]]
@@ -222,7 +255,14 @@ class LayerBuffers:
         if self.bound < 0:
             raise ScError(SC_EINVAL, "sc_out_bound")
         u8 = dict(dtype=torch.uint8, device=device)
-        self.table = torch.empty(max(sc_hash_bytes(n), 16), **u8)
+        self.grid_dims, self.epoch = grid_dims, 0
+        if grid_dims is None:
+            self.table = torch.empty(max(sc_hash_bytes(n), 16), **u8)
+        else:
+            if self.mode != SC_SUBM or sc_grid_bytes(*grid_dims) == 0:
+                raise ScError(SC_EINVAL, "sc_grid_bytes")
+            self.table = torch.empty(sc_grid_bytes(*grid_dims), **u8)
+            sc_grid_clear(self.table, grid_dims)
         self.kmap = torch.empty(max(sc_kmap_bytes(n, K, stride, mode), 16), **u8)
         self.scratch = torch.empty(max(sc_kmap_scratch_bytes(n, K, stride, mode), 16), **u8)
         self.workspace = torch.empty(max(sc_conv_workspace_bytes(K, C_in, C_out, dtype), 16), **u8)
@@ -233,9 +273,21 @@ class LayerBuffers:
         self.feat_out = torch.empty((max(self.bound, 1), C_out), dtype=self.out_dtype, device=device)
 
     def hash_build(self, coords, stream=None):
-        sc_hash_build(coords, self.table, self.counts, stream)
+        """Location table over `coords`: the hash table, or the dense array if grid_dims was given."""
+        if self.grid_dims is None:
+            sc_hash_build(coords, self.table, self.counts, stream)
+        else:
+            self.epoch += 1
+            if self.epoch >= 1 << 32:
+                sc_grid_clear(self.table, self.grid_dims, stream)
+                self.epoch = 1
+            sc_grid_build(coords, self.table, self.grid_dims, self.epoch, self.counts, stream)
 
     def kmap_build(self, coords, stream=None):
+        if self.grid_dims is not None:
+            sc_kmap_build_grid(coords, self.table, self.grid_dims, self.epoch, self.K, self.kmap, self.counts, stream)
+            self.out_coords = coords
+            return
         sc_kmap_build(coords, self.table, self.K, self.stride, self.mode,
                       None if self.mode == SC_SUBM else self.out_coords, self.kmap,
                       self.scratch, self.counts, stream)

@@ -54,9 +54,8 @@ __host__ __device__ inline uint32_t probe_slot(uint64_t key, uint32_t t, uint32_
 
 // capacity: power of two >= 4n (load factor <= 1/4 keeps probe chains short), at least 1024 slots
 inline uint64_t hash_capacity(int64_t n) {
-    static const int mult = getenv("SC_HASH_MULT") ? atoi(getenv("SC_HASH_MULT")) : 4;
     uint64_t cap = 1024;
-    while (cap < (uint64_t)mult * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
+    while (cap < 4ull * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
     return cap;
 }
 
@@ -162,7 +161,8 @@ extern __device__ long long* g_trace_buf;
 enum KernelId {
     KID_TABLE_FILL = 0, KID_HASH_INSERT, KID_HASH_LOOKUP, KID_KMAP_HEADER, KID_KMAP_SUBM, KID_FILL_I32,
     KID_STRIDED_INSERT, KID_STRIDED_FLAGS, KID_SCAN_BLOCKS, KID_STRIDED_PAIRS, KID_KMAP_FROM_OFT,
-    KID_COUNT_PAIRS, KID_EXPORT, KID_WEIGHT_PACK, KID_CONV_MFMA, KID_CONV_F32, KID_MISC, KID_COUNT
+    KID_COUNT_PAIRS, KID_EXPORT, KID_WEIGHT_PACK, KID_CONV_MFMA, KID_CONV_F32, KID_GRID_CLEAR, KID_GRID_INSERT,
+    KID_GRID_LOOKUP, KID_KMAP_GRID, KID_MISC, KID_COUNT
 };
 extern bool g_profile_on;
 // A fresh pair of events for one launch of `kernel_id`; false if none could be created.

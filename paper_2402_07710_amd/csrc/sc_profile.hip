@@ -23,7 +23,8 @@ std::vector<hipEvent_t> g_pool;      // events ready for reuse
 const char* const KERNEL_NAMES[KID_COUNT] = {
     "k_table_fill", "k_hash_insert", "k_hash_lookup", "k_kmap_header", "k_kmap_subm", "k_strided_fill",
     "k_strided_insert", "k_strided_flags", "k_scan_blocks", "k_strided_pairs", "k_masks_from_table",
-    "k_count_pairs", "k_export", "k_weight_pack", "k_conv_mfma", "k_conv_f32", "misc"};
+    "k_count_pairs", "k_export", "k_weight_pack", "k_conv_mfma", "k_conv_f32", "k_grid_clear", "k_grid_insert",
+    "k_grid_lookup", "k_kmap_subm_grid", "misc"};
 
 hipEvent_t take_event() {
     if (!g_pool.empty()) {

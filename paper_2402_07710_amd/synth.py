@@ -216,20 +216,21 @@ def weights(k3: int, c_in: int, c_out: int, dtype: str, seed: int) -> np.ndarray
 # --------------------------------------------------------------------------------------------
 CONFIGS = {
     # name: (coords builder, K, stride, mode, C_in, C_out, dtype)
+    # box = (B, X, Y, Z): the voxel grid the coordinates are confined to
     "cfg1": dict(coords=lambda: uniform_cells(2000, 64, seed=0), K=3, stride=1, mode="subm",
-                 C_in=16, C_out=16, dtype="f32"),
+                 C_in=16, C_out=16, dtype="f32", box=(1, 64, 64, 64)),
     "cfg2": dict(coords=lambda: lidar_scene(0), K=3, stride=1, mode="subm",
-                 C_in=32, C_out=32, dtype="f16"),
+                 C_in=32, C_out=32, dtype="f16", box=(1, 1408, 1600, 41)),
     "cfg3": dict(coords=lambda: lidar_scene(0), K=2, stride=2, mode="strided",
-                 C_in=32, C_out=64, dtype="f16"),
+                 C_in=32, C_out=64, dtype="f16", box=(1, 1408, 1600, 41)),
     "cfg4": dict(coords=lambda: lidar_batch([0, 1, 2, 3]), K=3, stride=1, mode="subm",
-                 C_in=64, C_out=64, dtype="bf16"),
+                 C_in=64, C_out=64, dtype="bf16", box=(4, 1408, 1600, 41)),
     "cfg5": dict(coords=lambda: indoor_scene(0), K=3, stride=1, mode="subm",
-                 C_in=128, C_out=128, dtype="f16"),
+                 C_in=128, C_out=128, dtype="f16", box=(1, 512, 512, 512)),
     # the ~100k-voxel C=64 fp16 submanifold layer the target statement names: three sweeps of
     # one scene (sensor displaced in 1 m steps), same local structure as cfg2
     "target64": dict(coords=lambda: lidar_scene(0, n_sweeps=3), K=3, stride=1, mode="subm",
-                     C_in=64, C_out=64, dtype="f16"),
+                     C_in=64, C_out=64, dtype="f16", box=(1, 1408, 1600, 41)),
 }
 
 
@@ -241,7 +242,7 @@ def make_config(name: str, seed: int = 0) -> dict:
     k3 = spec["K"] ** 3
     return dict(
         name=name, coords=coords, K=spec["K"], stride=spec["stride"], mode=spec["mode"],
-        C_in=spec["C_in"], C_out=spec["C_out"], dtype=spec["dtype"],
+        C_in=spec["C_in"], C_out=spec["C_out"], dtype=spec["dtype"], box=spec["box"],
         feat=features(len(coords), spec["C_in"], spec["dtype"], seed),
         weight=weights(k3, spec["C_in"], spec["C_out"], spec["dtype"], seed),
     )

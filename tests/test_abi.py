@@ -55,6 +55,12 @@ def test_size_queries(lib):
     assert lib.sc_kmap_scratch_bytes(6400, 2, 2, binding.SC_STRIDED) > 32768 * 16 + 6400 * 4
     assert lib.sc_conv_workspace_bytes(3, 64, 64, binding.SC_F16) == 27 * 64 * 64 * 2
     assert lib.sc_conv_workspace_bytes(3, 16, 16, binding.SC_F32) == 0
+    # dense location table: one 8-byte cell per site
+    assert lib.sc_grid_bytes(1, 1408, 1600, 41) == 1408 * 1600 * 41 * 8
+    assert lib.sc_grid_bytes(2, 3, 5, 7) == 1792                       # 210 cells, rounded up to 256 bytes
+    assert lib.sc_grid_bytes(0, 4, 4, 4) == 0 and lib.sc_grid_bytes(1, 4, -4, 4) == 0
+    assert lib.sc_grid_bytes(1, 65536, 4, 4) == 0                      # a side beyond the coordinate range
+    assert lib.sc_grid_bytes(1, 65535, 65535, 3) == 0                  # more than 2^33 sites
 
 
 def test_host_side_argument_errors(lib):
@@ -72,5 +78,13 @@ def test_host_side_argument_errors(lib):
                            binding.SC_BF16, 96, 1 << 20, None) == binding.SC_EINVAL  # output type mismatch
     assert lib.sc_conv_fwd(16, 10, 32, 48, 10, 64, 1 << 20, 80, 3, 1, binding.SC_SUBM, 32, 32, binding.SC_F16,
                            binding.SC_F16, 96, 16, None) == binding.SC_ECAP          # workspace too small
+    gb = lib.sc_grid_bytes(1, 8, 8, 8)
+    assert lib.sc_grid_build(16, 10, 32, gb, 1, 8, 8, 8, 0, 48, None) == binding.SC_EINVAL       # epoch 0 is "never"
+    assert lib.sc_grid_build(16, 10, 32, gb - 1, 1, 8, 8, 8, 1, 48, None) == binding.SC_ECAP
+    assert lib.sc_grid_build(16, 10, 32, gb, 1, 8, 0, 8, 1, 48, None) == binding.SC_EINVAL
+    assert lib.sc_grid_clear(None, gb, 1, 8, 8, 8, None) == binding.SC_EINVAL
+    assert lib.sc_grid_lookup(32, 1, 8, 8, 8, 0, 16, 4, 48, None) == binding.SC_EINVAL
+    assert lib.sc_kmap_build_grid(16, 10, 32, gb, 1, 8, 8, 8, 1, 2, 64, 1 << 20, 80, None) == binding.SC_EINVAL  # even K
+    assert lib.sc_kmap_build_grid(16, 10, 32, gb, 1, 8, 8, 8, 1, 3, 64, 8, 80, None) == binding.SC_ECAP
     assert binding.strerror(binding.SC_EDUP) == "duplicate input coordinate"
     assert binding.strerror(12345) == "unknown status"

@@ -27,11 +27,12 @@ def to_dev(x_f32: np.ndarray, dtype: str):
     return torch.from_numpy(np.ascontiguousarray(x_f32)).to(DEV).to(TDT[dtype]).contiguous()
 
 
-def run_layer(coords, feat, weight, K, stride, mode, dtype, out_dtype=None):
-    """Whole layer on the GPU.  Returns (buffers, counts, out_coords np, feat_out np float64)."""
+def run_layer(coords, feat, weight, K, stride, mode, dtype, out_dtype=None, grid_dims=None):
+    """Whole layer on the GPU.  Returns (buffers, counts, out_coords np, feat_out np float64).
+    grid_dims: use the dense location table over that box instead of the hash table."""
     n = len(coords)
     C_in, C_out = weight.shape[1], weight.shape[2]
-    buf = sc.LayerBuffers(n, K, stride, mode, C_in, C_out, dtype, out_dtype, device=DEV)
+    buf = sc.LayerBuffers(n, K, stride, mode, C_in, C_out, dtype, out_dtype, device=DEV, grid_dims=grid_dims)
     d_coords = torch.from_numpy(np.ascontiguousarray(coords, dtype=np.int32)).to(DEV).reshape(-1, 4)
     d_feat = to_dev(feat.reshape(n, C_in), dtype)
     d_w = to_dev(weight, dtype)
@@ -68,11 +69,11 @@ def rel_err(got, ref):
     return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30)) if ref.size else 0.0
 
 
-def check_layer(coords, K, stride, mode, C_in, C_out, dtype, seed=0, out_dtype=None, threads=8):
+def check_layer(coords, K, stride, mode, C_in, C_out, dtype, seed=0, out_dtype=None, threads=8, grid_dims=None):
     n = len(coords)
     feat = synth.features(n, C_in, dtype, seed)
     weight = synth.weights(K ** 3, C_in, C_out, dtype, seed)
-    buf, h, out_coords, out = run_layer(coords, feat, weight, K, stride, mode, dtype, out_dtype)
+    buf, h, out_coords, out = run_layer(coords, feat, weight, K, stride, mode, dtype, out_dtype, grid_dims)
     ref_km = oracle.kmap(coords, K, stride, mode)
     assert h.n_in == n and h.n_out == ref_km["n_out"] and h.n_pairs == ref_km["offset_start"][-1]
     assert list(h.per_offset[:K ** 3]) == list(np.diff(ref_km["offset_start"]))
@@ -134,6 +135,99 @@ def test_hash_reports_duplicates_and_range():
     # a clean build clears the latch
     sc.sc_hash_build(torch.from_numpy(coords).to(DEV), table, counts)
     assert sc.sc_counts_read(counts).status == 0
+
+
+# ---- dense location table ---------------------------------------------------------------------
+@pytest.mark.parametrize("n,box", [(1, (1, 4, 4, 4)), (63, (3, 8, 8, 8)), (2000, (3, 64, 64, 64)), (50000, (3, 64, 64, 41))])
+def test_grid_finds_every_key(n, box):
+    say(f"grid n={n} box={box}")
+    coords = synth.uniform_cells(n, min(box[1:]), seed=n)
+    coords[:, 0] = np.arange(n) % box[0]
+    d_coords = torch.from_numpy(coords).to(DEV)
+    grid = torch.empty(sc.sc_grid_bytes(*box), dtype=torch.uint8, device=DEV)
+    sc.sc_grid_clear(grid, box)
+    counts = torch.zeros(sc.COUNTS_BYTES + 8, dtype=torch.uint8, device=DEV)
+    sc.sc_grid_build(d_coords, grid, box, 1, counts)
+    h = sc.sc_counts_read(counts)
+    assert h.n_in == n and h.status == 0
+    rows = torch.empty(n, dtype=torch.int32, device=DEV)
+    sc.sc_grid_lookup(grid, box, 1, d_coords, rows)
+    assert torch.equal(rows.cpu(), torch.arange(n, dtype=torch.int32))
+    # another epoch sees nothing; queries outside the box are absent, not errors
+    sc.sc_grid_lookup(grid, box, 2, d_coords, rows)
+    assert bool((rows == -1).all())
+    outside = coords.copy()
+    outside[:, 3] += box[3]
+    outside[::2, 1] = -1
+    sc.sc_grid_lookup(grid, box, 1, torch.from_numpy(outside).to(DEV), rows)
+    assert bool((rows == -1).all())
+    present = {tuple(r): i for i, r in enumerate(coords.tolist())}
+    shifted = coords.copy()
+    shifted[:, 3] = (shifted[:, 3] + 1) % box[3]
+    want = np.array([present.get(tuple(r), -1) for r in shifted.tolist()], dtype=np.int32)
+    sc.sc_grid_lookup(grid, box, 1, torch.from_numpy(shifted).to(DEV), rows)
+    assert np.array_equal(rows.cpu().numpy(), want)
+
+
+def test_grid_reports_duplicates_and_range():
+    """The dense build stores blindly; the kernel-map build, which reads every row's own cell,
+    reports rows outside the box and rows that share a coordinate."""
+    say("grid errors")
+    box = (2, 16, 16, 16)
+    coords = synth.uniform_cells(500, 16, seed=1)
+    grid = torch.empty(sc.sc_grid_bytes(*box), dtype=torch.uint8, device=DEV)
+    sc.sc_grid_clear(grid, box)
+    counts = torch.zeros(sc.COUNTS_BYTES + 8, dtype=torch.uint8, device=DEV)
+    kmap = torch.empty(sc.sc_kmap_bytes(500, 3, 1, "subm"), dtype=torch.uint8, device=DEV)
+
+    def status_of(c, epoch):
+        d = torch.from_numpy(c).to(DEV)
+        sc.sc_grid_build(d, grid, box, epoch, counts)
+        sc.sc_kmap_build_grid(d, grid, box, epoch, 3, kmap, counts)
+        return sc.sc_counts_read(counts, check=False).status
+
+    dup = coords.copy()
+    dup[400] = dup[17]
+    assert status_of(dup, 1) == sc.SC_EDUP
+    for epoch, (col, val) in enumerate([(2, 16), (2, -1), (0, 2), (3, 65535)], start=2):
+        bad = coords.copy()
+        bad[3, col] = val
+        assert status_of(bad, epoch) == sc.SC_ERANGE, (col, val)
+    # a clean build clears the latch, and the cells of the failed builds are stale
+    assert status_of(coords, 9) == 0
+    rows = torch.empty(500, dtype=torch.int32, device=DEV)
+    sc.sc_grid_lookup(grid, box, 9, torch.from_numpy(coords).to(DEV), rows)
+    assert torch.equal(rows.cpu(), torch.arange(500, dtype=torch.int32))
+
+
+@pytest.mark.parametrize("K", [1, 3, 5, 7])
+@pytest.mark.parametrize("n", [1, 65, 1000])
+def test_grid_layer_small(K, n):
+    say(f"grid layer K={K} n={n}")
+    box = (2, 12, 12, 12)
+    coords = synth.uniform_cells(n, 12, seed=K + n)
+    coords[:, 0] = np.arange(n) % 2
+    check_layer(coords, K, 1, "subm", 32, 32, "f16", seed=K, grid_dims=box)
+
+
+def test_grid_reuse_across_builds_without_clearing():
+    """Several different voxel sets through ONE array: every build must only see its own cells."""
+    say("grid epochs")
+    box = (1, 20, 20, 20)
+    n_max = 3000
+    buf = sc.LayerBuffers(n_max, 3, 1, "subm", 32, 32, "f16", device=DEV, grid_dims=box)
+    for it, n in enumerate([3000, 700, 2500, 64, 1]):
+        coords = synth.uniform_cells(n, 20, seed=100 + it)
+        b = sc.LayerBuffers(n, 3, 1, "subm", 32, 32, "f16", device=DEV, grid_dims=box)
+        b.table, b.epoch = buf.table, buf.epoch            # the same array, the running epoch counter
+        d_coords = torch.from_numpy(coords).to(DEV)
+        b.hash_build(d_coords)
+        b.kmap_build(d_coords)
+        buf.epoch = b.epoch
+        h = b.read_counts()
+        ref_km = oracle.kmap(coords, 3, 1, "subm")
+        assert h.n_pairs == ref_km["offset_start"][-1]
+        assert_maps_equal(exported_map(b, h), coords, ref_km, exact_order=True)
 
 
 # ---- whole layers, small: several tiles and a ragged tail --------------------------------------
@@ -321,6 +415,30 @@ def test_named_config_full(name):
     err = check_layer(cfg["coords"], cfg["K"], cfg["stride"], cfg["mode"], cfg["C_in"], cfg["C_out"], cfg["dtype"],
                       threads=16)
     say(f"  {name}: N={len(cfg['coords'])} max rel err {err:.3e}")
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "target64", "cfg5"])
+def test_named_config_dense_table(name):
+    """The submanifold configurations again with the dense location table over the config's box:
+    the kernel map must be the oracle's, bit for bit (cfg5: the map only, its outputs are checked
+    with the hash-table build below - the convolution does not know which table made the map)."""
+    say(f"config {name}, dense table")
+    cfg = synth.make_config(name)
+    if name != "cfg5":
+        err = check_layer(cfg["coords"], cfg["K"], cfg["stride"], cfg["mode"], cfg["C_in"], cfg["C_out"], cfg["dtype"],
+                          threads=16, grid_dims=cfg["box"])
+        say(f"  {name}: max rel err {err:.3e}")
+        return
+    coords = cfg["coords"]
+    n = len(coords)
+    buf = sc.LayerBuffers(n, 3, 1, "subm", 128, 128, "f16", device=DEV, grid_dims=cfg["box"])
+    d_coords = torch.from_numpy(coords).to(DEV)
+    buf.hash_build(d_coords)
+    buf.kmap_build(d_coords)
+    h = buf.read_counts()
+    ref_km = oracle.kmap(coords, 3, 1, "subm")
+    assert h.n_pairs == ref_km["offset_start"][-1]
+    assert_maps_equal(exported_map(buf, h), coords, ref_km, exact_order=True)
 
 
 def test_cfg5_full_map_and_sampled_outputs():
