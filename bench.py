@@ -8,7 +8,7 @@ ms per layer, the per-phase split, the roofline of the kernel that takes the mos
 (durations from HIP events recorded around every kernel launch, on the launch's stream), and the
 CPU oracle timed on this host's cores for the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|target64]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3k3|cfg4|cfg5|cfg1|target64|cfg2-stage] [--table hash|grid]
 """
 from __future__ import annotations
 
@@ -304,6 +304,30 @@ def main() -> int:
         "launch": "hip graph replay" if graph is not None else "eager", "ms_per_step_eager": ms_per_step_eager,
         "phases_ms": phases, "kernels": per_kernel, "roofline": roofline,
     }
+
+    # the same layer with the other location table (same steps, same checks), for comparison
+    other = "grid" if args.table == "hash" else "hash"
+    if mode == "subm":
+        buf2 = sc.LayerBuffers(N, K, stride, mode, C_in, C_out, dtype, device=dev,
+                               grid_dims=cfg["box"] if other == "grid" else None)
+
+        def step2():
+            buf2.hash_build(d_coords, stream)
+            buf2.kmap_build(d_coords, stream)
+            buf2.conv_fwd(d_feat, d_w, stream)
+
+        for _ in range(args.warmup + 1):
+            step2()
+        if buf2.read_counts().n_pairs != P or not torch.equal(buf2.feat_out[:N_out], buf.feat_out[:N_out]):
+            raise RuntimeError("the two location tables give different layers")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step2()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - t0) * 1e3 / args.steps
+        out["other_table"] = {"table": other, "ms_per_step": ms2, "value": flops / (ms2 * 1e-3) / 1e12, "unit": "TFLOP/s"}
+        del buf2
 
     if not args.no_cpu_baseline:
         import oracle

@@ -128,8 +128,10 @@ int sc_grid_lookup(const void* d_grid, int32_t B, int32_t X, int32_t Y, int32_t 
  * Section III-D for strided layers: cell index floor(p/s), in-cell offset, distinct output
  * cells counted and numbered) ------------------------------------------------------------- */
 
-/* Upper bound on output rows for n inputs: n for SC_SUBM and for SC_STRIDED with K == stride
- * (for SC_INVERSE: the n fine rows themselves). */
+/* Upper bound on output rows for n inputs: n for SC_SUBM; n * ceil(K/stride)^3 for SC_STRIDED
+ * (an input p belongs to every cell q with p = q*stride + d, d in [0,K)^3: one cell when
+ * K == stride, up to ceil(K/stride)^3 otherwise); for SC_INVERSE the n fine rows themselves.
+ * -1 if the combination is not supported (see sc_kmap_build) or the bound exceeds SC_N_MAX. */
 int64_t sc_out_bound(int64_t n, int K, int stride, int mode);
 
 /* Bytes of the kernel-map blob and of the scratch buffer sc_kmap_build needs (0 = unsupported). */
@@ -138,14 +140,16 @@ size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode);
 
 /* Build the kernel map.
  *   d_table       table built by sc_hash_build over the same d_coords (required for SC_SUBM;
- *                 ignored for SC_STRIDED with K == stride, may be NULL there - but repeated
+ *                 ignored for SC_STRIDED, may be NULL there - but repeated
  *                 input coordinates are only detected by sc_hash_build)
- *   mode          SC_SUBM (stride must be 1, K odd, K <= SC_K_MAX) or SC_STRIDED (K == stride,
- *                 2 <= K <= 4; other K/stride combinations return SC_EINVAL)
+ *   mode          SC_SUBM (stride must be 1, K odd, K <= SC_K_MAX) or SC_STRIDED (2 <= K <=
+ *                 SC_K_MAX, 1 <= stride <= K, no padding: input p pairs with output cell q at
+ *                 offset d iff p = q*stride + d; K == stride <= 4 is the down-sampling layer of
+ *                 Section III-B / III-D and has its own faster build)
  *   d_out_coords  [sc_out_bound][4]; receives the output coordinates.  SC_SUBM: may be NULL
  *                 (outputs are the inputs, same order).  SC_STRIDED: required; output o is the
- *                 o-th distinct cell in order of first occurrence in the input, so the result
- *                 does not depend on thread timing.
+ *                 o-th distinct cell in order of first occurrence (input rows ascending, then
+ *                 offsets ascending), so the result does not depend on thread timing.
  *   d_kmap        opaque blob, kmap_bytes >= sc_kmap_bytes(...).  It holds the offset table of
  *                 Section III-C.2 (for every output row and offset the paired input row or -1),
  *                 tile-major: 64 consecutive output rows per tile, offset-major inside a tile,

@@ -109,6 +109,7 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     SC_MARK(0);
     int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
+    if (xcd_unit(blockIdx.x, gridDim.x) * NT * TILE >= n_out) return;   // no rows here: the whole workgroup leaves
     const int64_t row = tile * TILE + q * 16 + r;
     const bool group_ok = tile * TILE + q * 16 < n_out;             // uniform per wavefront
 
@@ -227,6 +228,9 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     SC_MARK(0);
     int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
+    // the grid covers the caller's row capacity; a workgroup whose tiles all lie past the rows
+    // that exist leaves at once (the same decision in every wavefront, before any barrier)
+    if (xcd_unit(blockIdx.x, gridDim.x) * NWV * TILE >= n_out) return;
     const bool tile_ok = tile * TILE < n_out;
 
     uint32_t mg[4] = {0u, 0u, 0u, 0u};

@@ -290,12 +290,94 @@ k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
     if (r == (int32_t)i) out_coords[o] = make_int4(c.x, qx, qy, qz);
 }
 
+// ---- strided layers with K != stride -------------------------------------------------------------
+// An input p pairs with output cell q at offset d whenever p = q*s + d, d in [0,K)^3 (the
+// enumeration of Algorithm 1's getOutputCoord with no padding), so it can belong to up to
+// MAXC = ceil(K/s)^3 cells.  Its valid (offset, cell) candidates are numbered j = 0.. in
+// ascending offset order; candidate id c = i*MAXC + j therefore orders all candidates by input
+// row and then by offset, and a cell's number is the rank of its lowest candidate id among all
+// cells' lowest ids: the same first-occurrence numbering as for K == stride, found with the same
+// flag / prefix kernels run over candidates instead of inputs.
+template <typename F>
+__device__ inline void for_each_candidate(const int4 c, int K, int s, F&& f) {
+    int j = 0;
+    for (int dx = 0; dx < K; ++dx) {
+        const int tx = c.y - dx;
+        if (tx < 0 || tx % s) continue;
+        for (int dy = 0; dy < K; ++dy) {
+            const int ty = c.z - dy;
+            if (ty < 0 || ty % s) continue;
+            for (int dz = 0; dz < K; ++dz) {
+                const int tz = c.w - dz;
+                if (tz < 0 || tz % s) continue;
+                f(j++, (dx * K + dy) * K + dz, tx / s, ty / s, tz / s);
+            }
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_gstrided_insert(const int4* __restrict__ coords, int64_t n, int K, int s, int maxc, uint4* oslots, uint32_t omask,
+                  int32_t* __restrict__ cand_slot, sc_counts* counts) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int4 c = coords[i];
+    int32_t* mine = cand_slot + i * maxc;
+    for (int j = 0; j < maxc; ++j) mine[j] = -1;
+    if (!in_domain4(c.x, c.y, c.z, c.w)) {
+        latch_status(counts, SC_ERANGE);
+        return;
+    }
+    for_each_candidate(c, K, s, [&](int j, int, int qx, int qy, int qz) {
+        const uint64_t key = pack_key(c.x, qx, qy, qz);
+        int32_t myslot = -1;
+        for (uint32_t t = 0; t <= omask + REHASH_MAX; ++t) {
+            const uint32_t slot = probe_slot(key, t, omask);
+            const uint64_t cur = atomicCAS(reinterpret_cast<unsigned long long*>(&oslots[slot]),
+                                           (unsigned long long)KEY_EMPTY, (unsigned long long)key);
+            if (cur == KEY_EMPTY || cur == key) {
+                myslot = (int32_t)slot;
+                break;
+            }
+        }
+        if (myslot >= 0) atomicMin(reinterpret_cast<int32_t*>(&oslots[myslot]) + 2, (int32_t)(i * maxc + j));
+        else latch_status(counts, SC_EFULL);
+        mine[j] = myslot;
+    });
+}
+
+__global__ void __launch_bounds__(256)
+k_gstrided_pairs(const int4* __restrict__ coords, int64_t n, int K, int s, int maxc,
+                 const int32_t* __restrict__ cand_slot, const uint4* __restrict__ oslots,
+                 const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
+                 const int32_t* __restrict__ block_prefix, int32_t* __restrict__ nbr,
+                 int4* __restrict__ out_coords, KmapHeader* hdr, KmapHeader hdr_value) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) *hdr = hdr_value;
+    if (i >= n) return;
+    const int4 c = coords[i];
+    if (!in_domain4(c.x, c.y, c.z, c.w)) return;
+    const int K3 = K * K * K;
+    for_each_candidate(c, K, s, [&](int j, int k, int qx, int qy, int qz) {
+        const int32_t sl = cand_slot[i * maxc + j];
+        if (sl < 0) return;
+        const int32_t r = (int32_t)oslots[sl].z;               // the cell's first candidate
+        const int32_t o = block_prefix[r >> 10] + word_prefix[r >> 6] +
+                          __popcll(flagword[r >> 6] & ((1ull << (r & 63)) - 1ull));
+        // one input per (output row, offset): a plain store
+        nbr[((int64_t)(o >> 6) * K3 + k) * TILE + (o & 63)] = (int32_t)i;
+        if (r == (int32_t)(i * maxc + j)) out_coords[o] = make_int4(c.x, qx, qy, qz);
+    });
+}
+
 // Group masks of a finished offset table: one wavefront per tile votes on every offset line.
 __global__ void __launch_bounds__(256)
-k_masks_from_table(const int32_t* __restrict__ nbr, int K3, int mw, int64_t tiles, uint32_t* __restrict__ gmask) {
+k_masks_from_table(const int32_t* __restrict__ nbr, int K3, int mw, int64_t tiles, uint32_t* __restrict__ gmask,
+                   const sc_counts* __restrict__ counts, int inverse) {
     const int lane = threadIdx.x & 63;
     const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= tiles) return;
+    // tiles past the last output row (inverse maps: the last fine row) are never read
+    if (tile >= tiles || tile * TILE >= (inverse ? counts->n_in : counts->n_out)) return;
     const int32_t* tile_nbr = nbr + tile * (int64_t)K3 * TILE;
     for (int wi = 0; wi < mw; ++wi) {
         uint32_t word = 0;                 // lanes 0..3: the mask word of group `lane`
@@ -400,12 +482,23 @@ k_transpose_scatter(const int32_t* __restrict__ nbr, int K3, const sc_counts* __
     }
 }
 
+// candidates per input of a strided layer: ceil(K/s)^3
+static int strided_maxc(int K, int stride) {
+    const int m = (K + stride - 1) / stride;
+    return m * m * m;
+}
+
 static bool kmap_args_ok(int64_t n, int K, int stride, int mode) {
     if (n < 0 || n > SC_N_MAX || K < 1 || K > SC_K_MAX) return false;
     if (mode == SC_SUBM) return stride == 1 && (K % 2) == 1;
-    if (mode == SC_STRIDED || mode == SC_INVERSE) return K == stride && K >= 2 && K <= 4;
+    if (mode == SC_INVERSE) return K == stride && K >= 2 && K <= 4;
+    if (mode == SC_STRIDED) {
+        if (K < 2 || stride < 1 || stride > K) return false;
+        return n * (int64_t)strided_maxc(K, stride) <= SC_N_MAX;     // candidate ids and output rows fit
+    }
     return false;
 }
+static bool strided_fast(int K, int stride) { return K == stride && K <= 4; }
 
 }  // namespace sc
 
@@ -413,7 +506,7 @@ using namespace sc;
 
 extern "C" int64_t sc_out_bound(int64_t n, int K, int stride, int mode) {
     if (!kmap_args_ok(n, K, stride, mode)) return -1;
-    return n;
+    return mode == SC_STRIDED ? n * (int64_t)strided_maxc(K, stride) : n;
 }
 
 extern "C" size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode) {
@@ -424,7 +517,7 @@ extern "C" size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode) {
 extern "C" size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode) {
     if (!kmap_args_ok(n, K, stride, mode)) return 0;
     if (mode == SC_SUBM) return 256;
-    return strided_scratch(nullptr, n).bytes;
+    return strided_scratch(nullptr, sc_out_bound(n, K, stride, mode)).bytes;    // one entry per candidate
 }
 
 extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
@@ -474,6 +567,36 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         return SC_OK;
     }
 
+    if (!strided_fast(K, stride)) {
+        // strided, general K and stride: the same pipeline over candidates (input, offset)
+        const int maxc = strided_maxc(K, stride);
+        const int64_t nc = n * maxc;
+        StridedScratch g = strided_scratch(d_scratch, nc);
+        const uint64_t gcap = (uint64_t)g.omask + 1;
+        const int64_t gvec = (int64_t)((L.bytes - L.off_nbr) / 16);
+        {
+            int64_t work = (int64_t)gcap > gvec ? (int64_t)gcap : gvec;
+            unsigned fb = (unsigned)((work + 255) / 256);
+            if (fb > 4096) fb = 4096;
+            SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, g.oslots, gcap, (int4*)nbr, gvec);
+        }
+        const int64_t gblk = (nc + 1023) / 1024;
+        const unsigned gg = (unsigned)((n + 255) / 256);
+        SC_LAUNCH(KID_STRIDED_INSERT, k_gstrided_insert, dim3(gg), dim3(256), 0, s, (const int4*)d_coords, n, K, stride,
+                  maxc, g.oslots, g.omask, g.slot_of, d_counts);
+        SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)gblk), dim3(1024), 0, s, nc,
+                  (const int32_t*)g.slot_of, (const uint4*)g.oslots, g.flagword, g.word_prefix, g.block_sum);
+        SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)g.block_sum,
+                  g.block_prefix, gblk, d_counts);
+        SC_LAUNCH(KID_STRIDED_PAIRS, k_gstrided_pairs, dim3(gg), dim3(256), 0, s, (const int4*)d_coords, n, K, stride,
+                  maxc, (const int32_t*)g.slot_of, (const uint4*)g.oslots, (const uint64_t*)g.flagword,
+                  (const int32_t*)g.word_prefix, (const int32_t*)g.block_prefix, nbr, (int4*)d_out_coords,
+                  (KmapHeader*)d_kmap, h);
+        SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
+                  (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask, (const sc_counts*)d_counts, 0);
+        return SC_OK;
+    }
+
     // strided, K == stride
     StridedScratch sc_ = strided_scratch(d_scratch, n);
     const uint64_t cap = (uint64_t)sc_.omask + 1;
@@ -497,7 +620,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
               (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, nbr, (int4*)d_out_coords,
               (KmapHeader*)d_kmap, h);
     SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
-              (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask);
+              (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask, (const sc_counts*)d_counts, 0);
     return SC_OK;
 }
 
@@ -527,7 +650,7 @@ extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int strid
     if (gb > 4096) gb = 4096;
     SC_LAUNCH(KID_MISC, k_transpose_scatter, dim3(gb), dim3(256), 0, s, nbr, L.K3, d_counts, inv_nbr);
     SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
-              (const int32_t*)inv_nbr, L.K3, L.mw, L.tiles, inv_mask);
+              (const int32_t*)inv_nbr, L.K3, L.mw, L.tiles, inv_mask, d_counts, 1);
     return SC_OK;
 }
 

@@ -223,6 +223,9 @@ CONFIGS = {
                  C_in=32, C_out=32, dtype="f16", box=(1, 1408, 1600, 41)),
     "cfg3": dict(coords=lambda: lidar_scene(0), K=2, stride=2, mode="strided",
                  C_in=32, C_out=64, dtype="f16", box=(1, 1408, 1600, 41)),
+    # the down-sampling layer most encoders use: 3x3x3 kernel, stride 2, no padding (K != stride)
+    "cfg3k3": dict(coords=lambda: lidar_scene(0), K=3, stride=2, mode="strided",
+                   C_in=32, C_out=64, dtype="f16", box=(1, 1408, 1600, 41)),
     "cfg4": dict(coords=lambda: lidar_batch([0, 1, 2, 3]), K=3, stride=1, mode="subm",
                  C_in=64, C_out=64, dtype="bf16", box=(4, 1408, 1600, 41)),
     "cfg5": dict(coords=lambda: indoor_scene(0), K=3, stride=1, mode="subm",

@@ -46,6 +46,13 @@ def test_size_queries(lib):
     assert lib.sc_hash_bytes(-1) == 0
     assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
     assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
+    # K != stride: an input can sit in ceil(K/s)^3 output cells
+    assert lib.sc_out_bound(500, 3, 2, binding.SC_STRIDED) == 500 * 8
+    assert lib.sc_out_bound(500, 3, 1, binding.SC_STRIDED) == 500 * 27
+    assert lib.sc_out_bound(500, 5, 5, binding.SC_STRIDED) == 500
+    assert lib.sc_out_bound(500, 2, 3, binding.SC_STRIDED) == -1     # stride > K leaves inputs unused
+    assert lib.sc_out_bound(1 << 24, 3, 2, binding.SC_STRIDED) == -1  # more candidates than rows a map can hold
+    assert lib.sc_out_bound(500, 3, 2, binding.SC_INVERSE) == -1
     assert lib.sc_out_bound(500, 2, 1, binding.SC_SUBM) == -1      # even K has no centre
     assert lib.sc_out_bound(500, 3, 2, binding.SC_SUBM) == -1      # submanifold stride is 1
     assert lib.sc_kmap_bytes(500, 9, 1, binding.SC_SUBM) == 0

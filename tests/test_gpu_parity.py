@@ -249,6 +249,23 @@ def test_strided_small(K, s, n):
     check_layer(coords, K, s, "strided", 8, 24, "f32", seed=n)
 
 
+@pytest.mark.parametrize("K,s", [(3, 2), (3, 1), (4, 2), (5, 2), (5, 3), (2, 1), (5, 5), (7, 7)])
+@pytest.mark.parametrize("n", [1, 65, 900])
+def test_strided_general_kernel_and_stride(K, s, n):
+    """K != stride (and K == stride beyond 4): every input belongs to up to ceil(K/s)^3 output
+    cells; output numbering by first occurrence (input row, then offset) must be the oracle's."""
+    say(f"strided general K={K} s={s} n={n}")
+    coords = synth.uniform_cells(n, 14, seed=K * 100 + s * 10 + n)
+    coords[:, 0] = np.arange(n) % 2
+    check_layer(coords, K, s, "strided", 32, 32, "f16", seed=n)
+
+
+def test_strided_general_on_lidar_scene():
+    say("strided K=3 s=2 on the cfg2 voxel set")
+    coords = synth.lidar_scene(0)
+    check_layer(coords, 3, 2, "strided", 32, 64, "f16", threads=16)
+
+
 @pytest.mark.parametrize("K", [1, 5, 7])
 def test_subm_other_kernel_sizes(K):
     say(f"subm K={K}")
