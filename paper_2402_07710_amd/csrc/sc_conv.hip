@@ -205,7 +205,16 @@ __device__ __align__(256) uint4 g_zero_row[32];      // 512 bytes: a row of up t
 //    multiplies are skipped, so all waits are exact counts.
 // Accumulators (64 rows x C_out per wavefront) never leave the registers.  KS = C_in/32,
 // CB = C_out/16.
-template <int DT, int K3, int KS, int CB, int NWV, int D>
+// RC = 1 gathers rows lane-contiguously.  The texture path serves a 64-lane load four consecutive
+// lanes per cycle when they read one 64-byte segment and one lane per cycle when they do not
+// (measured: 65 cycles per instruction in the operand's lane order, where consecutive lanes
+// belong to different rows; 18 with four consecutive lanes on the four 16-byte pieces of one
+// row).  The rows then arrive in "load layout" and pass through a small per-wavefront LDS area
+// (swizzled slots) right before use to come back in operand layout.  It pays where the gather
+// dominates (64 channels: -9 % on ~10^5 voxels); for 128 channels the extra LDS traffic costs
+// more than the gather saves, and an in-register shuffle (lane-swap + quad-permute
+// instructions, 20 VALU operations per 16 bytes) was measured slower than either.
+template <int DT, int K3, int KS, int CB, int NWV, int D, int RC>
 __global__ void __launch_bounds__(64 * NWV, 2)
 k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
               const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
@@ -218,13 +227,16 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     constexpr int WPT = WK / NTH;                     // uint4 per thread per W[k]
     constexpr int CBG = CB < 4 ? CB : 4;              // weight operands held at a time
     static_assert(CB % CBG == 0, "whole operand batches");
-    extern __shared__ __align__(16) uint4 smem[];     // w_lds[2][WK] | e_lds[NWV][K3][64]
+    constexpr int RB = C_in * 2;                      // bytes per feature row
+    extern __shared__ __align__(16) uint4 smem[];     // w_lds[2][WK] | stage[NWV][16 rows] | e_lds[NWV][K3][64]
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
     const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NWV + wv;
     uint4* w_lds = smem;
-    int32_t* e_lds = reinterpret_cast<int32_t*>(smem + 2 * WK) + wv * (K3 * TILE);
+    constexpr int STAGE = RC ? 16 * RB : 0;          // bytes of the per-wavefront staging area
+    char* stage = reinterpret_cast<char*>(smem + 2 * WK) + wv * STAGE;
+    int32_t* e_lds = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(smem + 2 * WK) + NWV * STAGE) + wv * (K3 * TILE);
     SC_MARK(0);
     int64_t n_out = *n_out_ptr;
     if (n_out > n_out_cap) n_out = n_out_cap;
@@ -260,15 +272,27 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
 #pragma unroll
         for (int i = 0; i < WPT; ++i) wr[j][i] = wsrc[(int64_t)j * WK + i * NTH];
 
+    // which row of a group and which 16-byte piece of a 32-channel slice this lane gathers: the
+    // operand's own lane order, or (RC) four consecutive lanes on the four pieces of one row
+    const int lrow = RC ? lane >> 2 : r, lpiece = RC ? lane & 3 : qq;
+    // staging area of one group: [16 rows][RB bytes], the 16-byte slots of a row swizzled with the
+    // row number so that both the row-wise stores and the column-wise operand reads spread over the banks
+    auto swz = [](int row) -> int { return KS == 1 ? ((row >> 1) & 3) : (row & 7); };
+    int st_w[KS], st_r[KS];
+#pragma unroll
+    for (int i = 0; i < KS; ++i) {
+        st_w[i] = lrow * RB + (((i * 4 + lpiece) ^ swz(lrow)) << 4);
+        st_r[i] = r * RB + (((i * 4 + qq) ^ swz(r)) << 4);
+    }
     auto rowptr = [&](int32_t e) -> const uint4* {
-        return (e >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e * C_in) : g_zero_row) + qq;
+        return (e >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e * C_in) : g_zero_row) + lpiece;
     };
     uint4 fb[D][4][KS];
 #pragma unroll
     for (int j = 0; j < D && j < K3; ++j) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const uint4* frow = rowptr(e_lds[j * TILE + g * 16 + r]);
+            const uint4* frow = rowptr(e_lds[j * TILE + g * 16 + lrow]);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) fb[j][g][ks] = frow[ks * 4];
         }
@@ -293,9 +317,20 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
         int32_t e4[4] = {-1, -1, -1, -1};
         if (more) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) e4[g] = e_lds[(k + D) * TILE + g * 16 + r];
+            for (int g = 0; g < 4; ++g) e4[g] = e_lds[(k + D) * TILE + g * 16 + lrow];
         }
         __builtin_amdgcn_sched_barrier(0);            // the fetches are issued here, not next to their use
+        // the rows of this offset: load layout -> operand layout through the staging area, one group
+        // after the other (a wavefront's LDS operations execute in order, so the area is reused at once)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if (RC && ((mg[g] >> k) & 1u)) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<uint4*>(stage + st_w[ks]) = fb[k % D][g][ks];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) fb[k % D][g][ks] = *reinterpret_cast<const uint4*>(stage + st_r[ks]);
+            }
+        }
         const uint4* wk = w_lds + (k & 1) * WK + lane;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -484,11 +519,12 @@ static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream
     return SC_OK;
 }
 
-template <int DT, int K3, int KS, int CB, int NWV, int D>
+template <int DT, int K3, int KS, int CB, int NWV, int D, int RC>
 static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D>;
-    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (size_t)NWV * K3 * TILE * sizeof(int32_t);
+    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, RC>;
+    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (RC ? (size_t)NWV * 16 * KS * 64 : 0) +
+                       (size_t)NWV * K3 * TILE * sizeof(int32_t);
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -506,14 +542,14 @@ static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream
                            const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
                            const int64_t* counts, int64_t n_out_cap, bool* handled) {
     *handled = true;
-#define SC_STREAM(K3V, KSV, CBV, NWV, DV) \
-    return launch_stream<DT, K3V, KSV, CBV, NWV, DV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
-    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4, 4, 3);
-    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1);
-    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3);
-    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2);
-    if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2);
-    if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1);
+#define SC_STREAM(K3V, KSV, CBV, NWV, DV, RCV) \
+    return launch_stream<DT, K3V, KSV, CBV, NWV, DV, RCV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
+    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4, 4, 3, 1);
+    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1, 0);
+    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3, 0);
+    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2, 0);
+    if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2, 0);
+    if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1, 0);
 #undef SC_STREAM
     *handled = false;
     return SC_OK;
