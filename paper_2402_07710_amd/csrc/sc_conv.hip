@@ -234,7 +234,7 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     const int r = lane & 15, qq = lane >> 4;
     const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NWV + wv;
     uint4* w_lds = smem;
-    constexpr int STAGE = RC ? 16 * RB : 0;          // bytes of the per-wavefront staging area
+    constexpr int STAGE = RC ? 4 * 16 * RB : 0;      // bytes of the per-wavefront staging area (one part per group)
     char* stage = reinterpret_cast<char*>(smem + 2 * WK) + wv * STAGE;
     int32_t* e_lds = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(smem + 2 * WK) + NWV * STAGE) + wv * (K3 * TILE);
     SC_MARK(0);
@@ -320,15 +320,21 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
             for (int g = 0; g < 4; ++g) e4[g] = e_lds[(k + D) * TILE + g * 16 + lrow];
         }
         __builtin_amdgcn_sched_barrier(0);            // the fetches are issued here, not next to their use
-        // the rows of this offset: load layout -> operand layout through the staging area, one group
-        // after the other (a wavefront's LDS operations execute in order, so the area is reused at once)
+        // the rows of this offset: load layout -> operand layout through the staging area (all stores,
+        // then all loads: one LDS round trip per step; a wavefront's LDS operations execute in order,
+        // so the area can be reused at the next step without further ado)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             if (RC && ((mg[g] >> k) & 1u)) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<uint4*>(stage + st_w[ks]) = fb[k % D][g][ks];
+                for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<uint4*>(stage + g * (16 * RB) + st_w[ks]) = fb[k % D][g][ks];
+            }
+        }
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) fb[k % D][g][ks] = *reinterpret_cast<const uint4*>(stage + st_r[ks]);
+        for (int g = 0; g < 4; ++g) {
+            if (RC && ((mg[g] >> k) & 1u)) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) fb[k % D][g][ks] = *reinterpret_cast<const uint4*>(stage + g * (16 * RB) + st_r[ks]);
             }
         }
         const uint4* wk = w_lds + (k & 1) * WK + lane;
@@ -523,7 +529,7 @@ template <int DT, int K3, int KS, int CB, int NWV, int D, int RC>
 static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
     auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, RC>;
-    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (RC ? (size_t)NWV * 16 * KS * 64 : 0) +
+    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (RC ? (size_t)NWV * 4 * 16 * KS * 64 : 0) +
                        (size_t)NWV * K3 * TILE * sizeof(int32_t);
     static bool attr_set = false;
     if (!attr_set) {
