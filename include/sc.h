@@ -79,8 +79,8 @@ typedef struct sc_counts {
 /* ---- location table (Section III-C.1; the paper offers a dense array or a hash table, this
  * library uses an open-addressing hash table keyed on the packed 64-bit (b,x,y,z)) ---------- */
 
-/* Bytes of the table for n keys: 16 bytes per slot, capacity = power of two >= 4n and >= 1024
- * slots, so the load factor stays <= 1/4. */
+/* Bytes of the table for n keys: 16 bytes per slot, capacity = power of two >= 8n and >= 1024
+ * slots, so the load factor stays <= 1/8. */
 size_t sc_hash_bytes(int64_t n);
 
 /* Build the table coordinate -> row index over d_coords [n][4] (b,x,y,z).  Also resets

@@ -39,10 +39,10 @@ def test_counts_struct_layout():
 def test_size_queries(lib):
     # 16-byte slots, capacity = power of two >= 4n (at least 1024)
     assert lib.sc_hash_bytes(0) == 1024 * 16
-    assert lib.sc_hash_bytes(256) == 1024 * 16
-    assert lib.sc_hash_bytes(257) == 2048 * 16
-    assert lib.sc_hash_bytes(1000) == 4096 * 16
-    assert lib.sc_hash_bytes(1025) == 8192 * 16
+    assert lib.sc_hash_bytes(128) == 1024 * 16
+    assert lib.sc_hash_bytes(129) == 2048 * 16
+    assert lib.sc_hash_bytes(1000) == 8192 * 16
+    assert lib.sc_hash_bytes(1025) == 16384 * 16
     assert lib.sc_hash_bytes(-1) == 0
     assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
     assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
