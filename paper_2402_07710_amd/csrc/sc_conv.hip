@@ -354,9 +354,19 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
                     }
                 }
             }
-            if (more) {             // this slice is free: refill it with the rows of offset k + D
+            if (more && D == 1) {   // this slice is free: refill it with the rows of offset k + D
 #pragma unroll
                 for (int g = 0; g < 4; ++g) fb[k % D][g][ks] = rowptr(e4[g])[ks * 4];
+            }
+        }
+        if (more && D > 1) {
+            // with a deeper ring there is no hurry: refill the whole slot at once, so that the loads
+            // which share a cache line (the 64-byte slices of one row) are issued back to back
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint4* frow = rowptr(e4[g]);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) fb[k % D][g][ks] = frow[ks * 4];
             }
         }
         if (k + 1 < K3) {
