@@ -502,6 +502,73 @@ k_conv_f32(const float* __restrict__ feat, const float* __restrict__ w, float* _
     }
 }
 
+// fp32 layers with few channels (C_in = 16*CI16 <= 64, C_out = 16*CB <= 64, K^3 <= 32): the same
+// instruction, loads batched.  A lane reads 16 bytes (4 channels) of its row per 16-channel chunk
+// and feeds component j to the j-th of four multiplies, so input channel 16c + 4q + j sits at
+// position q of multiply (c, j); the weight operand is read to match.  The offsets that exist are
+// taken four at a time: their four table entries are in flight together, then all their feature
+// loads, so a group costs two dependent round trips per batch instead of two per offset.
+template <int CI16, int CB>
+__global__ void __launch_bounds__(256)
+k_conv_f32_small(const float* __restrict__ feat, const float* __restrict__ w, float* __restrict__ out,
+                 const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr, int K3,
+                 const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
+    constexpr int C_in = 16 * CI16, C_out = 16 * CB, NB = 4;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int r = lane & 15, qq = lane >> 4;
+    const int64_t tile = blockIdx.x;
+    int64_t n_out = *n_out_ptr;
+    if (n_out > n_out_cap) n_out = n_out_cap;
+    const int64_t row = tile * TILE + q * 16 + r;
+    if (tile * TILE + q * 16 >= n_out) return;                       // uniform per wavefront
+
+    f32x4 acc[CB];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int32_t* line = nbr + tile * (int64_t)K3 * TILE + q * 16 + r;
+    uint32_t m = __builtin_amdgcn_readfirstlane(gmask[tile * 4 + q]);
+    while (m) {
+        int kk[NB];
+        int32_t e[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            kk[j] = m ? __builtin_ctz(m) : -1;
+            if (m) m &= m - 1;
+            e[j] = kk[j] >= 0 ? line[kk[j] * TILE] : -1;
+        }
+        float4 f[NB][CI16];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const float4* frow = reinterpret_cast<const float4*>(feat + (int64_t)(e[j] < 0 ? 0 : e[j]) * C_in) + qq;
+#pragma unroll
+            for (int c = 0; c < CI16; ++c) f[j][c] = e[j] >= 0 ? frow[c * 4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (kk[j] >= 0) {                                        // uniform
+                const float* wk = w + (int64_t)kk[j] * C_in * C_out + r;
+#pragma unroll
+                for (int c = 0; c < CI16; ++c) {
+                    const float b[4] = {f[j][c].x, f[j][c].y, f[j][c].z, f[j][c].w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float* wrow = wk + (int64_t)(c * 16 + 4 * qq + t) * C_out;
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(wrow[cb * 16], b[t], acc[cb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (row < n_out) {
+        float* orow = out + row * C_out;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+            *reinterpret_cast<float4*>(orow + cb * 16 + qq * 4) = make_float4(acc[cb][0], acc[cb][1], acc[cb][2], acc[cb][3]);
+    }
+}
+
 template <int DT, int K3, int KS, int CB, int NT>
 static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
@@ -615,6 +682,18 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
 
     if (dtype_in == SC_F32) {
         if (C_out > 256) return SC_EINVAL;
+        if (L.K3 <= 32 && C_in % 16 == 0 && C_in <= 64 && C_out % 16 == 0 && C_out <= 64) {
+#define SC_F32_SMALL(CI, CBV)                                                                                         \
+    if (C_in == 16 * CI && C_out == 16 * CBV) {                                                                       \
+        SC_LAUNCH(KID_CONV_F32, (k_conv_f32_small<CI, CBV>), dim3((unsigned)tiles), dim3(256), 0, s,                  \
+                  (const float*)d_feat_in, (const float*)d_weight, (float*)d_feat_out, gmask, nbr, L.K3, n_out_ptr,   \
+                  n_out_cap);                                                                                         \
+        return SC_OK;                                                                                                 \
+    }
+            SC_F32_SMALL(1, 1) SC_F32_SMALL(1, 2) SC_F32_SMALL(2, 1) SC_F32_SMALL(2, 2) SC_F32_SMALL(2, 4)
+            SC_F32_SMALL(4, 2) SC_F32_SMALL(4, 4)
+#undef SC_F32_SMALL
+        }
         SC_LAUNCH(KID_CONV_F32, k_conv_f32, dim3((unsigned)tiles), dim3(256), 0, s, (const float*)d_feat_in,
                   (const float*)d_weight, (float*)d_feat_out, gmask, nbr, L.K3, L.mw, C_in, C_out, n_out_ptr,
                   n_out_cap);

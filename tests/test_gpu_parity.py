@@ -276,7 +276,8 @@ def test_subm_other_kernel_sizes(K):
 
 @pytest.mark.parametrize("dtype,C_in,C_out", [("f16", 32, 32), ("f16", 64, 64), ("f16", 128, 128), ("f16", 256, 48),
                                               ("bf16", 64, 64), ("bf16", 32, 256), ("bf16", 128, 16),
-                                              ("f32", 16, 16), ("f32", 3, 100), ("f32", 70, 130)])
+                                              ("f32", 16, 16), ("f32", 3, 100), ("f32", 70, 130),
+                                              ("f32", 32, 64), ("f32", 64, 32), ("f32", 64, 64), ("f32", 16, 32)])
 def test_channel_shapes(dtype, C_in, C_out):
     say(f"channels {dtype} {C_in}->{C_out}")
     coords = synth.uniform_cells(3000, 18, seed=C_in + C_out)     # about half the cells active: ~14 pairs/voxel
