@@ -121,9 +121,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--table", choices=["hash", "grid"], default="hash",
-                    help="location table: the open-addressing hash table (default, what the metric is quoted on) or "
-                         "the dense array over the workload's voxel box (submanifold workloads only)")
+    ap.add_argument("--table", choices=["hash", "grid", "fused"], default="hash",
+                    help="location table: the open-addressing hash table (default, what the metric is quoted on), "
+                         "the dense array over the workload's voxel box (submanifold workloads only), or the dense "
+                         "array with the look-ups fused into the convolution (no kernel map; 3x3x3 16-bit layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", choices=["auto", "on", "off"], default="off",
                     help="replay the step from a captured HIP graph instead of launching eagerly "
@@ -157,14 +158,17 @@ def main() -> int:
     d_coords = torch.from_numpy(coords).to(dev)
     d_feat = torch.from_numpy(cfg["feat"]).to(dev).to(tdt).contiguous()
     d_w = torch.from_numpy(cfg["weight"]).to(dev).to(tdt).contiguous()
-    if args.table == "grid" and mode != "subm":
+    if args.table != "hash" and mode != "subm":
         print("bench.py: --table grid applies to submanifold workloads only", file=sys.stderr)
         return 2
     buf = sc.LayerBuffers(N, K, stride, mode, C_in, C_out, dtype, device=dev,
-                          grid_dims=cfg["box"] if args.table == "grid" else None)
+                          grid_dims=cfg["box"] if args.table != "hash" else None)
     stream = torch.cuda.current_stream()
 
     def step():
+        if args.table == "fused":
+            buf.layer_fused(d_coords, d_feat, d_w, stream)
+            return
         buf.hash_build(d_coords, stream)
         buf.kmap_build(d_coords, stream)
         buf.conv_fwd(d_feat, d_w, stream)
@@ -178,6 +182,8 @@ def main() -> int:
         del src, dst
 
     step()
+    if args.table == "fused":
+        buf.kmap_build(d_coords, stream)          # once, outside the timed region: only to count the pairs
     h = buf.read_counts()
     if h.status != 0:
         raise RuntimeError(f"device status {h.status}")
@@ -198,9 +204,12 @@ def main() -> int:
             with torch.cuda.stream(gstream):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=gstream):
-                    buf.hash_build(d_coords, gstream)
-                    buf.kmap_build(d_coords, gstream)
-                    buf.conv_fwd(d_feat, d_w, gstream)
+                    if args.table == "fused":
+                        buf.layer_fused(d_coords, d_feat, d_w, gstream)
+                    else:
+                        buf.hash_build(d_coords, gstream)
+                        buf.kmap_build(d_coords, gstream)
+                        buf.conv_fwd(d_feat, d_w, gstream)
             torch.cuda.synchronize()
             ref = buf.feat_out[:N_out].clone()
             buf.feat_out.zero_()
@@ -244,9 +253,14 @@ def main() -> int:
         ev[i][0].record(stream)
         buf.hash_build(d_coords, stream)
         ev[i][1].record(stream)
-        buf.kmap_build(d_coords, stream)
+        if args.table != "fused":
+            buf.kmap_build(d_coords, stream)
         ev[i][2].record(stream)
-        buf.conv_fwd(d_feat, d_w, stream)
+        if args.table == "fused":
+            sc.sc_conv_fwd_grid(d_feat, d_coords, buf.table, buf.grid_dims, buf.epoch, d_w, buf.feat_out, K,
+                                buf.workspace, stream)
+        else:
+            buf.conv_fwd(d_feat, d_w, stream)
         ev[i][3].record(stream)
     torch.cuda.synchronize()
     phases = {name: float(np.median([e[j].elapsed_time(e[j + 1]) for e in ev]))
@@ -270,6 +284,8 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload if args.table == "hash" else args.workload + "-grid", {}).get(dominant)
+        if args.table == "fused":
+            traffic = None                                   # no counter run of the fused kernels is on file
     if dominant in ("k_conv_mfma", "k_conv_f32"):
         # the contraction: flops of the pairs that exist against the matrix-core (or fp32 ALU) peak
         peak = PEAK_MFMA_TFLOPS if dominant == "k_conv_mfma" else PEAK_FP32_TFLOPS
@@ -306,7 +322,7 @@ def main() -> int:
     }
 
     # the same layer with the other location table (same steps, same checks), for comparison
-    other = "grid" if args.table == "hash" else "hash"
+    other = "grid" if args.table == "hash" else "hash"          # (fused is compared with the hash table too)
     if mode == "subm":
         buf2 = sc.LayerBuffers(N, K, stride, mode, C_in, C_out, dtype, device=dev,
                                grid_dims=cfg["box"] if other == "grid" else None)

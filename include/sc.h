@@ -221,6 +221,21 @@ int sc_conv_fwd(const void* d_feat_in, int64_t n_map,
                 void* d_workspace, size_t workspace_bytes,
                 void* stream);
 
+/* Fused form of the last two steps for 3x3x3 submanifold layers over a dense location table
+ * (Section III-C.2 and III-C.3 in one pass): the convolution looks the 27 neighbours of its rows
+ * up in the table built by sc_grid_build(d_coords, n, ..., epoch) itself, so no kernel map is
+ * built, stored or read.  Output row i belongs to d_coords row i; d_feat_out [n][C_out] is fully
+ * overwritten.  16-bit layers only (dtype_in SC_F16 / SC_BF16), (C_in, C_out) one of (32,32),
+ * (64,64), (128,128), (32,64), (64,128); anything else returns SC_EINVAL - use the three calls.
+ * Nothing is validated here (no counts block): rows outside the box get only their centre term,
+ * repeated coordinates are not noticed; sc_kmap_build_grid is the call that checks. */
+int sc_conv_fwd_grid(const void* d_feat_in, const int32_t* d_coords, int64_t n,
+                     const void* d_grid, size_t grid_bytes, int32_t B, int32_t X, int32_t Y, int32_t Z,
+                     uint32_t epoch,
+                     const void* d_weight, void* d_feat_out,
+                     int K, int C_in, int C_out, int dtype_in, int dtype_out,
+                     void* d_workspace, size_t workspace_bytes, void* stream);
+
 /* ---- reading results back ------------------------------------------------------------------ */
 
 /* Fill n_pairs and per_offset from the kernel map (d_kmap may be NULL to skip that), copy the

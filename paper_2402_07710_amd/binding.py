@@ -28,7 +28,8 @@ TORCH_DTYPES = {SC_F32: torch.float32, SC_F16: torch.float16, SC_BF16: torch.bfl
 SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
-           "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid"]
+           "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid",
+           "sc_conv_fwd_grid"]
 
 
 class ScCounts(ctypes.Structure):
@@ -85,6 +86,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_grid_build": (i32, [vp, i64, vp, sz, i32, i32, i32, i32, ctypes.c_uint32, vp, vp]),
         "sc_grid_lookup": (i32, [vp, i32, i32, i32, i32, ctypes.c_uint32, vp, i64, vp, vp]),
         "sc_kmap_build_grid": (i32, [vp, i64, vp, sz, i32, i32, i32, i32, ctypes.c_uint32, i32, vp, sz, vp, vp]),
+        "sc_conv_fwd_grid": (i32, [vp, vp, i64, vp, sz, i32, i32, i32, i32, ctypes.c_uint32, vp, vp, i32, i32, i32, i32, i32,
+                                   vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -182,6 +185,15 @@ def sc_kmap_build_grid(coords, grid, dims, epoch, K, kmap, counts, stream=None):
     _check(load().sc_kmap_build_grid(_ptr(coords), coords.shape[0], _ptr(grid), grid.numel() * grid.element_size(),
                                      *dims, epoch, K, _ptr(kmap), kmap.numel() * kmap.element_size(), _ptr(counts),
                                      _stream(stream)), "sc_kmap_build_grid")
+
+
+def sc_conv_fwd_grid(feat_in, coords, grid, dims, epoch, weight, feat_out, K, workspace, stream=None):
+    """Fused 3x3x3 submanifold layer over the dense table: no kernel map."""
+    C_in, C_out = weight.shape[1], weight.shape[2]
+    _check(load().sc_conv_fwd_grid(_ptr(feat_in), _ptr(coords), coords.shape[0], _ptr(grid),
+                                   grid.numel() * grid.element_size(), *dims, epoch, _ptr(weight), _ptr(feat_out), K,
+                                   C_in, C_out, DTYPES[feat_in.dtype], DTYPES[feat_out.dtype], _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)), "sc_conv_fwd_grid")
 
 
 def sc_kmap_transpose(kmap, n, K, stride, counts, kmap_inv, stream=None):
@@ -297,6 +309,13 @@ class LayerBuffers:
     def conv_fwd(self, feat_in, weight, stream=None):
         sc_conv_fwd(feat_in, weight, self.feat_out, self.kmap, self.counts, self.K, self.stride, self.mode,
                     self.workspace, stream)
+
+    def layer_fused(self, coords, feat_in, weight, stream=None):
+        """Dense table + fused look-up and convolution (3x3x3 submanifold layers, grid_dims given)."""
+        self.hash_build(coords, stream)
+        sc_conv_fwd_grid(feat_in, coords, self.table, self.grid_dims, self.epoch, weight, self.feat_out, self.K,
+                         self.workspace, stream)
+        self.out_coords = coords
 
     def layer(self, coords, feat_in, weight, stream=None):
         self.hash_build(coords, stream)

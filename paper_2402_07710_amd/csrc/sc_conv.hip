@@ -94,12 +94,17 @@ __device__ inline void store_acc(void* __restrict__ out, int out_f32, int64_t ro
 // copies the weights of all K3 offsets into LDS once, re-laying them out as MFMA operand tiles on
 // the way, so no separate packing pass is needed; meanwhile every wavefront has its K3 offset-table lines and then all its feature
 // gathers in flight.  KS = C_in/32, CB = C_out/16.
-template <int DT, int K3, int KS, int CB, int NT>
+// FUSED: there is no kernel map; the K^3 neighbours of a row are looked up in the dense location
+// table right here (one index computation and one 8-byte load each, all in flight together), and
+// the group's mask is a vote over what was found.  n_out_cap is then the number of rows.
+template <int DT, int K3, int KS, int CB, int NT, int FUSED>
 __global__ void __launch_bounds__(256 * NT)
 k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw, void* __restrict__ out, int out_f32,
-              const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
-              const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
+              const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
+    static_assert(!FUSED || K3 == 27, "fused look-ups: 3x3x3 layers");
+    const uint32_t* __restrict__ gmask = ms.gmask;
+    const int32_t* __restrict__ nbr = ms.nbr;
     constexpr int C_in = KS * 32, C_out = CB * 16;
     extern __shared__ __align__(16) uint4 w_lds[];                   // [K3][CB][KS][64]
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -107,8 +112,8 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NT + (wv >> 2);
     const int q = wv & 3;
     SC_MARK(0);
-    int64_t n_out = *n_out_ptr;
-    if (n_out > n_out_cap) n_out = n_out_cap;
+    int64_t n_out = n_out_cap;
+    if (!FUSED && *n_out_ptr < n_out) n_out = *n_out_ptr;
     if (xcd_unit(blockIdx.x, gridDim.x) * NT * TILE >= n_out) return;   // no rows here: the whole workgroup leaves
     const int64_t row = tile * TILE + q * 16 + r;
     const bool group_ok = tile * TILE + q * 16 < n_out;             // uniform per wavefront
@@ -116,7 +121,24 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     // the group's offset-table lines (all K3 of them) and its mask word: one round trip
     int32_t e[K3];
     uint32_t m = 0;
-    if (group_ok) {
+    if constexpr (FUSED) {
+        // the four lanes that serve a row look up every fourth offset each and trade the results
+        // through LDS (a wavefront's LDS operations execute in order: no barrier needed)
+        __shared__ int32_t found_s[FUSED ? 4 * NT : 1][28][16];
+        if (group_ok) {
+            int32_t part[7];
+            grid_neighbours_quarter<3>(ms, row, n_out, qq, part);
+#pragma unroll
+            for (int u = 0; u < 7; ++u) found_s[wv][qq + 4 * u][r] = part[u];
+#pragma unroll
+            for (int k = 0; k < K3; ++k) e[k] = found_s[wv][k][r];
+#pragma unroll
+            for (int k = 0; k < K3; ++k) m |= (__ballot(e[k] >= 0) != 0ull ? 1u : 0u) << k;
+        } else {
+#pragma unroll
+            for (int k = 0; k < K3; ++k) e[k] = -1;
+        }
+    } else if (group_ok) {
         const int32_t* line = nbr + tile * (int64_t)(K3 * TILE) + q * 16 + r;
 #pragma unroll
         for (int k = 0; k < K3; ++k) e[k] = line[k * TILE];
@@ -214,12 +236,15 @@ __device__ __align__(256) uint4 g_zero_row[32];      // 512 bytes: a row of up t
 // dominates (64 channels: -9 % on ~10^5 voxels); for 128 channels the extra LDS traffic costs
 // more than the gather saves, and an in-register shuffle (lane-swap + quad-permute
 // instructions, 20 VALU operations per 16 bytes) was measured slower than either.
-template <int DT, int K3, int KS, int CB, int NWV, int D, int RC>
+// FUSED: as in k_conv_rows16, the offset-table lines come from the dense location table directly.
+template <int DT, int K3, int KS, int CB, int NWV, int D, int RC, int FUSED>
 __global__ void __launch_bounds__(64 * NWV, 2)
 k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
-              const uint32_t* __restrict__ gmask, const int32_t* __restrict__ nbr,
-              const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
+              const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
+    static_assert(!FUSED || K3 == 27, "fused look-ups: 3x3x3 layers");
+    const uint32_t* __restrict__ gmask = ms.gmask;
+    const int32_t* __restrict__ nbr = ms.nbr;
     constexpr int NTH = 64 * NWV;
     constexpr int C_in = KS * 32, C_out = CB * 16;
     constexpr int WK = CB * KS * 64;                  // uint4 per packed W[k]
@@ -238,8 +263,8 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     char* stage = reinterpret_cast<char*>(smem + 2 * WK) + wv * STAGE;
     int32_t* e_lds = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(smem + 2 * WK) + NWV * STAGE) + wv * (K3 * TILE);
     SC_MARK(0);
-    int64_t n_out = *n_out_ptr;
-    if (n_out > n_out_cap) n_out = n_out_cap;
+    int64_t n_out = n_out_cap;
+    if (!FUSED && *n_out_ptr < n_out) n_out = *n_out_ptr;
     // the grid covers the caller's row capacity; a workgroup whose tiles all lie past the rows
     // that exist leaves at once (the same decision in every wavefront, before any barrier)
     if (xcd_unit(blockIdx.x, gridDim.x) * NWV * TILE >= n_out) return;
@@ -248,7 +273,20 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     uint32_t mg[4] = {0u, 0u, 0u, 0u};
     {   // the tile's offset-table lines -> LDS (read back below by other lanes of this wavefront)
         int32_t v[K3];
-        if (tile_ok) {
+        if constexpr (FUSED) {
+            if (tile_ok) {
+                grid_neighbours<3>(ms, tile * TILE + lane, n_out, v);
+#pragma unroll
+                for (int k = 0; k < K3; ++k) {
+                    const uint64_t vote = __ballot(v[k] >= 0);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) mg[g] |= (((vote >> (16 * g)) & 0xffffull) != 0ull ? 1u : 0u) << k;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < K3; ++k) v[k] = -1;
+            }
+        } else if (tile_ok) {
             const int32_t* line = nbr + tile * (int64_t)(K3 * TILE) + lane;
 #pragma unroll
             for (int k = 0; k < K3; ++k) v[k] = line[k * TILE];
@@ -569,10 +607,10 @@ k_conv_f32_small(const float* __restrict__ feat, const float* __restrict__ w, fl
     }
 }
 
-template <int DT, int K3, int KS, int CB, int NT>
+template <int DT, int K3, int KS, int CB, int NT, int FUSED>
 static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
-                         const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_rows16<DT, K3, KS, CB, NT>;
+                         const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
+    auto fn = k_conv_rows16<DT, K3, KS, CB, NT, FUSED>;
     const size_t lds = (size_t)K3 * CB * KS * 64 * sizeof(uint4);
     static bool attr_set = false;           // once per instantiation; the value never changes
     if (!attr_set) {
@@ -581,34 +619,36 @@ static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, con
         attr_set = true;
     }
     const dim3 grid(xcd_grid((tiles + NT - 1) / NT));
-    SC_LAUNCH(KID_CONV_MFMA, fn, grid, dim3(256 * NT), lds, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap);
+    SC_LAUNCH(KID_CONV_MFMA, fn, grid, dim3(256 * NT), lds, s, feat, wp, out, out_f32, ms, counts, n_out_cap);
     return SC_OK;
 }
 
 // Shapes whose packed weights fit in LDS as a whole.
-template <int DT>
+template <int DT, int FUSED>
 static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
-                           const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
-                           const int64_t* counts, int64_t n_out_cap, bool* handled) {
+                           const uint4* wp, void* out, int out_f32, const MapSource& ms, const int64_t* counts,
+                           int64_t n_out_cap, bool* handled) {
     *handled = true;
 #define SC_ROWS16(K3V, KSV, CBV, NTV) \
-    return launch_rows16<DT, K3V, KSV, CBV, NTV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
+    return launch_rows16<DT, K3V, KSV, CBV, NTV, FUSED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
     // four tiles per workgroup once every CU still gets a workgroup: the weights are re-laid out
     // half as often and no CU hosts two workgroups while another hosts one (cfg2: 11.9 -> 10.6 us)
     if (K3 == 27 && C_in == 32 && C_out == 32 && tiles >= 512) SC_ROWS16(27, 1, 2, 4);
     if (K3 == 27 && C_in == 32 && C_out == 32) SC_ROWS16(27, 1, 2, 2);
-    if (K3 == 8 && C_in == 32 && C_out == 64) SC_ROWS16(8, 1, 4, 2);
-    if (K3 == 8 && C_in == 32 && C_out == 32) SC_ROWS16(8, 1, 2, 2);
-    if (K3 == 8 && C_in == 64 && C_out == 64) SC_ROWS16(8, 2, 4, 2);
+    if constexpr (!FUSED) {
+        if (K3 == 8 && C_in == 32 && C_out == 64) SC_ROWS16(8, 1, 4, 2);
+        if (K3 == 8 && C_in == 32 && C_out == 32) SC_ROWS16(8, 1, 2, 2);
+        if (K3 == 8 && C_in == 64 && C_out == 64) SC_ROWS16(8, 2, 4, 2);
+    }
 #undef SC_ROWS16
     *handled = false;
     return SC_OK;
 }
 
-template <int DT, int K3, int KS, int CB, int NWV, int D, int RC>
+template <int DT, int K3, int KS, int CB, int NWV, int D, int RC, int FUSED>
 static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
-                         const uint32_t* gmask, const int32_t* nbr, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, RC>;
+                         const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
+    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, RC, FUSED>;
     const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (RC ? (size_t)NWV * 4 * 16 * KS * 64 : 0) +
                        (size_t)NWV * K3 * TILE * sizeof(int32_t);
     static bool attr_set = false;
@@ -618,24 +658,26 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
         attr_set = true;
     }
     SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + NWV - 1) / NWV)), dim3(64 * NWV), lds, s, feat, wp, out, out_f32,
-              gmask, nbr, counts, n_out_cap);
+              ms, counts, n_out_cap);
     return SC_OK;
 }
 
 // Shapes with a streaming kernel.
-template <int DT>
+template <int DT, int FUSED>
 static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
-                           const uint4* wp, void* out, int out_f32, const uint32_t* gmask, const int32_t* nbr,
-                           const int64_t* counts, int64_t n_out_cap, bool* handled) {
+                           const uint4* wp, void* out, int out_f32, const MapSource& ms, const int64_t* counts,
+                           int64_t n_out_cap, bool* handled) {
     *handled = true;
 #define SC_STREAM(K3V, KSV, CBV, NWV, DV, RCV) \
-    return launch_stream<DT, K3V, KSV, CBV, NWV, DV, RCV>(tiles, s, feat, wp, out, out_f32, gmask, nbr, counts, n_out_cap)
+    return launch_stream<DT, K3V, KSV, CBV, NWV, DV, RCV, FUSED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
     if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4, 4, 3, 1);
     if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1, 0);
     if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3, 0);
     if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2, 0);
-    if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2, 0);
-    if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1, 0);
+    if constexpr (!FUSED) {
+        if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2, 0);
+        if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1, 0);
+    }
 #undef SC_STREAM
     *handled = false;
     return SC_OK;
@@ -643,6 +685,32 @@ static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream
 
 static bool mfma_channels_ok(int C_in, int C_out) {
     return (C_in == 32 || C_in == 64 || C_in == 128 || C_in == 256) && C_out >= 16 && C_out <= 256 && C_out % 16 == 0;
+}
+
+// The 16-bit layer shapes with a dedicated kernel: small layers take their weights straight from
+// d_weight (re-laid out into LDS by the kernel), the others from the packed copy this makes in
+// the workspace.  *handled = false if the shape has no dedicated kernel.
+template <int FUSED>
+static int conv_16bit(int dtype_in, int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const void* d_feat_in,
+                      const void* d_weight, void* d_workspace, void* d_feat_out, int out_f32, const MapSource& ms,
+                      const int64_t* n_out_ptr, int64_t n_out_cap, bool* handled) {
+    const uint16_t* feat = (const uint16_t*)d_feat_in;
+    int rc = dtype_in == SC_F16 ? launch_resident<SC_F16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
+                                                                 d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled)
+                                : launch_resident<SC_BF16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
+                                                                  d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled);
+    if (*handled || rc != SC_OK) return rc;
+    const bool stream_shape = K3 == 27 && ((C_in == 64 && C_out == 64) || (C_in == 128 && C_out == 128) ||
+                                           (C_in == 32 && C_out == 64) || (C_in == 64 && C_out == 128));
+    const bool stream_shape8 = !FUSED && K3 == 8 && ((C_in == 64 && C_out == 128) || (C_in == 128 && C_out == 128));
+    if (!stream_shape && !stream_shape8) return SC_OK;
+    const int64_t pack_threads = (int64_t)K3 * (C_out / 16) * (C_in / 32) * 64;
+    SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
+              (const uint16_t*)d_weight, (uint4*)d_workspace, K3, C_in, C_out);
+    return dtype_in == SC_F16 ? launch_streamed<SC_F16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_workspace,
+                                                               d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled)
+                              : launch_streamed<SC_BF16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_workspace,
+                                                                d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled);
 }
 
 }  // namespace sc
@@ -705,35 +773,16 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
     if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
     const int out_f32 = dtype_out == SC_F32;
     static const bool force_any = getenv("SC_CONV_GENERIC") != nullptr;
-    if (!force_any) {           // small layers: weights go to LDS straight from d_weight
+    if (!force_any) {
         bool handled = false;
-        int rc;
-        if (dtype_in == SC_F16)
-            rc = launch_resident<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                         (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
-                                         n_out_cap, &handled);
-        else
-            rc = launch_resident<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                          (const uint4*)d_weight, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
-                                          n_out_cap, &handled);
+        const MapSource ms{gmask, nbr, nullptr, nullptr, GridDims{0, 0, 0, 0}, 0u};
+        const int rc = conv_16bit<0>(dtype_in, L.K3, C_in, C_out, tiles, s, d_feat_in, d_weight, d_workspace, d_feat_out,
+                                     out_f32, ms, n_out_ptr, n_out_cap, &handled);
         if (handled || rc != SC_OK) return rc;
     }
     const int64_t pack_threads = (int64_t)L.K3 * (C_out / 16) * (C_in / 32) * 64;
     SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
               (const uint16_t*)d_weight, (uint4*)d_workspace, L.K3, C_in, C_out);
-    if (!force_any) {
-        bool handled = false;
-        int rc;
-        if (dtype_in == SC_F16)
-            rc = launch_streamed<SC_F16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                         (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
-                                         n_out_cap, &handled);
-        else
-            rc = launch_streamed<SC_BF16>(L.K3, C_in, C_out, tiles, s, (const uint16_t*)d_feat_in,
-                                          (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, n_out_ptr,
-                                          n_out_cap, &handled);
-        if (handled || rc != SC_OK) return rc;
-    }
     if (dtype_in == SC_F16)
         SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_F16>, dim3((unsigned)tiles), dim3(256), 0, s,
                   (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
@@ -743,4 +792,29 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
                   (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
                   C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
     return SC_OK;
+}
+
+extern "C" int sc_conv_fwd_grid(const void* d_feat_in, const int32_t* d_coords, int64_t n, const void* d_grid,
+                                size_t grid_bytes, int32_t B, int32_t X, int32_t Y, int32_t Z, uint32_t epoch,
+                                const void* d_weight, void* d_feat_out, int K, int C_in, int C_out, int dtype_in,
+                                int dtype_out, void* d_workspace, size_t workspace_bytes, void* stream) {
+    const size_t gneed = sc_grid_bytes(B, X, Y, Z);
+    if (gneed == 0 || n < 0 || n > SC_N_MAX || epoch == 0 || K != 3) return SC_EINVAL;
+    if (d_weight == nullptr || d_grid == nullptr) return SC_EINVAL;
+    if (n > 0 && (d_feat_in == nullptr || d_feat_out == nullptr || d_coords == nullptr)) return SC_EINVAL;
+    if (!aligned16(d_feat_in) || !aligned16(d_weight) || !aligned16(d_feat_out) || !aligned16(d_grid) ||
+        !aligned16(d_coords) || !aligned16(d_workspace))
+        return SC_EINVAL;
+    if (dtype_in != SC_F16 && dtype_in != SC_BF16) return SC_EINVAL;
+    if (dtype_out != SC_F32 && dtype_out != dtype_in) return SC_EINVAL;
+    if (grid_bytes < gneed) return SC_ECAP;
+    const size_t need = sc_conv_workspace_bytes(K, C_in, C_out, dtype_in);
+    if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
+    if (n == 0) return SC_OK;
+    const MapSource ms{nullptr, nullptr, (const int4*)d_coords, (const unsigned long long*)d_grid, GridDims{B, X, Y, Z}, epoch};
+    bool handled = false;
+    const int rc = conv_16bit<1>(dtype_in, 27, C_in, C_out, (n + TILE - 1) / TILE, (hipStream_t)stream, d_feat_in, d_weight,
+                                 d_workspace, d_feat_out, dtype_out == SC_F32, ms, nullptr, n, &handled);
+    if (rc != SC_OK) return rc;
+    return handled ? SC_OK : SC_EINVAL;        // no fused kernel for this shape: use the three calls
 }

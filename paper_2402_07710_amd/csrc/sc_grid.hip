@@ -13,18 +13,6 @@
 
 namespace sc {
 
-struct GridDims {
-    int32_t B, X, Y, Z;
-};
-__host__ __device__ inline int64_t grid_cells(GridDims d) { return (int64_t)d.B * d.X * d.Y * d.Z; }
-__device__ inline bool grid_inside(GridDims d, int b, int x, int y, int z) {
-    return (unsigned)b < (unsigned)d.B && (unsigned)x < (unsigned)d.X && (unsigned)y < (unsigned)d.Y &&
-           (unsigned)z < (unsigned)d.Z;
-}
-__device__ inline int64_t grid_index(GridDims d, int b, int x, int y, int z) {
-    return (((int64_t)b * d.X + x) * d.Y + y) * d.Z + z;
-}
-
 __global__ void __launch_bounds__(256)
 k_grid_clear(uint4* __restrict__ blob16, int64_t n16) {
     const int64_t nthr = (int64_t)gridDim.x * blockDim.x;

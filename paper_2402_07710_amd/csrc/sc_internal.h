@@ -94,6 +94,85 @@ __device__ inline void latch_status(sc_counts* counts, int code) {
 // every slot <- {EMPTY, val_init}; optionally *counts reset (defined in sc_hash.hip)
 int launch_table_fill(uint4* slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in, hipStream_t s);
 
+// ---- dense location table (sc_grid.hip) -------------------------------------------------------
+// One 8-byte cell {row (low 32 bits), epoch (high 32 bits)} per site of the box, z fastest.
+struct GridDims {
+    int32_t B, X, Y, Z;
+};
+__host__ __device__ inline int64_t grid_cells(GridDims d) { return (int64_t)d.B * d.X * d.Y * d.Z; }
+__device__ inline bool grid_inside(GridDims d, int b, int x, int y, int z) {
+    return (unsigned)b < (unsigned)d.B && (unsigned)x < (unsigned)d.X && (unsigned)y < (unsigned)d.Y &&
+           (unsigned)z < (unsigned)d.Z;
+}
+__device__ inline int64_t grid_index(GridDims d, int b, int x, int y, int z) {
+    return (((int64_t)b * d.X + x) * d.Y + y) * d.Z + z;
+}
+
+// Where a convolution kernel finds the neighbours of its rows: the offset table of a kernel-map
+// blob (mask + nbr), or - fused layers - the dense location table itself, looked up on the fly.
+struct MapSource {
+    const uint32_t* gmask;
+    const int32_t* nbr;
+    const int4* coords;
+    const unsigned long long* cells;
+    GridDims dims;
+    uint32_t epoch;
+};
+// The K^3 neighbours of `row` (its own index at the centre), straight from the dense table:
+// what k_kmap_subm_grid stores as the row's column of the offset table.
+template <int K>
+__device__ inline void grid_neighbours(const MapSource& ms, int64_t row, int64_t n, int32_t (&e)[K * K * K]) {
+    constexpr int K3 = K * K * K, pad = (K - 1) / 2, centre = (K3 - 1) / 2;
+    const bool valid = row < n;
+    int4 c = make_int4(-1, 0, 0, 0);
+    if (valid) c = ms.coords[row];
+    const bool ok = valid && grid_inside(ms.dims, c.x, c.y, c.z, c.w);
+    const int64_t base = ok ? grid_index(ms.dims, c.x, c.y, c.z, c.w) : 0;
+    unsigned long long got[K3];
+    bool look[K3];
+#pragma unroll
+    for (int k = 0; k < K3; ++k) {
+        const int dx = k / (K * K) - pad, dy = (k / K) % K - pad, dz = k % K - pad;
+        look[k] = ok && k != centre && (unsigned)(c.y + dx) < (unsigned)ms.dims.X &&
+                  (unsigned)(c.z + dy) < (unsigned)ms.dims.Y && (unsigned)(c.w + dz) < (unsigned)ms.dims.Z;
+        got[k] = look[k] ? ms.cells[base + ((int64_t)dx * ms.dims.Y + dy) * ms.dims.Z + dz] : 0ull;
+    }
+#pragma unroll
+    for (int k = 0; k < K3; ++k) {
+        if (k == centre) e[k] = valid ? (int32_t)row : -1;
+        else e[k] = (look[k] && (uint32_t)(got[k] >> 32) == ms.epoch) ? (int32_t)(uint32_t)got[k] : -1;
+    }
+}
+
+// The same for every fourth offset only, k = first + 4u (u = 0..ceil(K^3/4)-1; entries past K^3 are
+// -1): four lanes that serve one row share the look-ups instead of repeating them.
+template <int K>
+__device__ inline void grid_neighbours_quarter(const MapSource& ms, int64_t row, int64_t n, int first,
+                                               int32_t (&e)[(K * K * K + 3) / 4]) {
+    constexpr int K3 = K * K * K, pad = (K - 1) / 2, centre = (K3 - 1) / 2, NQ = (K3 + 3) / 4;
+    const bool valid = row < n;
+    int4 c = make_int4(-1, 0, 0, 0);
+    if (valid) c = ms.coords[row];
+    const bool ok = valid && grid_inside(ms.dims, c.x, c.y, c.z, c.w);
+    const int64_t base = ok ? grid_index(ms.dims, c.x, c.y, c.z, c.w) : 0;
+    unsigned long long got[NQ];
+    bool look[NQ];
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int k = first + 4 * u;
+        const int dx = k / (K * K) - pad, dy = (k / K) % K - pad, dz = k % K - pad;
+        look[u] = ok && k < K3 && k != centre && (unsigned)(c.y + dx) < (unsigned)ms.dims.X &&
+                  (unsigned)(c.z + dy) < (unsigned)ms.dims.Y && (unsigned)(c.w + dz) < (unsigned)ms.dims.Z;
+        got[u] = look[u] ? ms.cells[base + ((int64_t)dx * ms.dims.Y + dy) * ms.dims.Z + dz] : 0ull;
+    }
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int k = first + 4 * u;
+        if (k == centre) e[u] = valid ? (int32_t)row : -1;
+        else e[u] = (look[u] && (uint32_t)(got[u] >> 32) == ms.epoch) ? (int32_t)(uint32_t)got[u] : -1;
+    }
+}
+
 // ---- kernel-map blob ------------------------------------------------------------------------
 // header | mask[T][4][mw] (uint32) | nbr[T][K3][TILE] (int32)
 // Outputs are cut into tiles of 64 consecutive rows.  nbr[t][k][j] is the input row paired with

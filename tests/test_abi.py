@@ -93,5 +93,11 @@ def test_host_side_argument_errors(lib):
     assert lib.sc_grid_lookup(32, 1, 8, 8, 8, 0, 16, 4, 48, None) == binding.SC_EINVAL
     assert lib.sc_kmap_build_grid(16, 10, 32, gb, 1, 8, 8, 8, 1, 2, 64, 1 << 20, 80, None) == binding.SC_EINVAL  # even K
     assert lib.sc_kmap_build_grid(16, 10, 32, gb, 1, 8, 8, 8, 1, 3, 64, 8, 80, None) == binding.SC_ECAP
+    assert lib.sc_conv_fwd_grid(16, 32, 10, 48, gb, 1, 8, 8, 8, 1, 64, 80, 5, 32, 32, binding.SC_F16, binding.SC_F16,
+                                96, 1 << 20, None) == binding.SC_EINVAL                 # 3x3x3 only
+    assert lib.sc_conv_fwd_grid(16, 32, 10, 48, gb, 1, 8, 8, 8, 1, 64, 80, 3, 32, 32, binding.SC_F32, binding.SC_F32,
+                                96, 1 << 20, None) == binding.SC_EINVAL                 # 16-bit layers only
+    assert lib.sc_conv_fwd_grid(16, 32, 10, 48, gb, 1, 8, 8, 8, 1, 64, 80, 3, 32, 32, binding.SC_F16, binding.SC_F16,
+                                96, 16, None) == binding.SC_ECAP                        # workspace too small
     assert binding.strerror(binding.SC_EDUP) == "duplicate input coordinate"
     assert binding.strerror(12345) == "unknown status"

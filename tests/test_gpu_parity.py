@@ -435,6 +435,42 @@ def test_named_config_full(name):
     say(f"  {name}: N={len(cfg['coords'])} max rel err {err:.3e}")
 
 
+@pytest.mark.parametrize("n,C_in,C_out,dtype", [(1, 32, 32, "f16"), (65, 64, 64, "bf16"), (1000, 32, 64, "f16"),
+                                                 (1500, 64, 128, "f16"), (700, 128, 128, "bf16")])
+def test_fused_dense_layer_small(n, C_in, C_out, dtype):
+    """sc_conv_fwd_grid (look-ups inside the convolution, no kernel map) against the oracle, incl.
+    voxels on the faces of the box and two batches."""
+    say(f"fused dense layer n={n} {C_in}->{C_out} {dtype}")
+    box = (2, 12, 12, 12)
+    coords = synth.uniform_cells(n, 12, seed=n)
+    coords[:, 0] = np.arange(n) % 2
+    feat = synth.features(n, C_in, dtype, 1)
+    weight = synth.weights(27, C_in, C_out, dtype, 1)
+    buf = sc.LayerBuffers(n, 3, 1, "subm", C_in, C_out, dtype, device=DEV, grid_dims=box)
+    buf.feat_out.fill_(float("nan"))
+    buf.layer_fused(torch.from_numpy(coords).to(DEV), to_dev(feat, dtype), to_dev(weight, dtype))
+    ref = oracle.conv(feat, weight, oracle.kmap(coords, 3, 1, "subm"), threads=8)
+    err = rel_err(buf.feat_out[:n].double().cpu().numpy(), ref)
+    assert err <= TOL[dtype], err
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4", "target64", "cfg5"])
+def test_fused_dense_layer_equals_three_call_layer(name):
+    """Same kernels, same order of operations: the fused layer's output must equal the
+    hash-table layer's output bit for bit (which the tests above and below hold to the oracle)."""
+    say(f"config {name}, fused dense layer")
+    cfg = synth.make_config(name)
+    n = len(cfg["coords"])
+    d_coords = torch.from_numpy(cfg["coords"]).to(DEV)
+    d_feat, d_w = to_dev(cfg["feat"], cfg["dtype"]), to_dev(cfg["weight"], cfg["dtype"])
+    a = sc.LayerBuffers(n, 3, 1, "subm", cfg["C_in"], cfg["C_out"], cfg["dtype"], device=DEV)
+    a.layer(d_coords, d_feat, d_w)
+    b = sc.LayerBuffers(n, 3, 1, "subm", cfg["C_in"], cfg["C_out"], cfg["dtype"], device=DEV, grid_dims=cfg["box"])
+    b.layer_fused(d_coords, d_feat, d_w)
+    torch.cuda.synchronize()
+    assert torch.equal(a.feat_out[:n], b.feat_out[:n])
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "target64", "cfg5"])
 def test_named_config_dense_table(name):
     """The submanifold configurations again with the dense location table over the config's box:
