@@ -169,8 +169,14 @@ def main() -> int:
         if args.table == "fused":
             buf.layer_fused(d_coords, d_feat, d_w, stream)
             return
-        buf.hash_build(d_coords, stream)
-        buf.kmap_build(d_coords, stream)
+        if mode == "strided":
+            # a strided layer looks nothing up in an input table (Section III-D builds the output side
+            # only): its step is map build + convolution; sc_hash_build would only add the check for
+            # repeated input coordinates
+            buf.kmap_build(d_coords, stream, standalone=True)
+        else:
+            buf.hash_build(d_coords, stream)
+            buf.kmap_build(d_coords, stream)
         buf.conv_fwd(d_feat, d_w, stream)
 
     if args.copy_calibration:
@@ -207,8 +213,11 @@ def main() -> int:
                     if args.table == "fused":
                         buf.layer_fused(d_coords, d_feat, d_w, gstream)
                     else:
-                        buf.hash_build(d_coords, gstream)
-                        buf.kmap_build(d_coords, gstream)
+                        if mode == "strided":
+                            buf.kmap_build(d_coords, gstream, standalone=True)
+                        else:
+                            buf.hash_build(d_coords, gstream)
+                            buf.kmap_build(d_coords, gstream)
                         buf.conv_fwd(d_feat, d_w, gstream)
             torch.cuda.synchronize()
             ref = buf.feat_out[:N_out].clone()
@@ -251,10 +260,11 @@ def main() -> int:
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     for i in range(args.steps):
         ev[i][0].record(stream)
-        buf.hash_build(d_coords, stream)
+        if mode != "strided":
+            buf.hash_build(d_coords, stream)
         ev[i][1].record(stream)
         if args.table != "fused":
-            buf.kmap_build(d_coords, stream)
+            buf.kmap_build(d_coords, stream, standalone=(mode == "strided"))
         ev[i][2].record(stream)
         if args.table == "fused":
             sc.sc_conv_fwd_grid(d_feat, d_coords, buf.table, buf.grid_dims, buf.epoch, d_w, buf.feat_out, K,

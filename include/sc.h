@@ -139,9 +139,12 @@ size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode);
 size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode);
 
 /* Build the kernel map.
- *   d_table       table built by sc_hash_build over the same d_coords (required for SC_SUBM;
- *                 ignored for SC_STRIDED, may be NULL there - but repeated
- *                 input coordinates are only detected by sc_hash_build)
+ *   d_table       table built by sc_hash_build over the same d_coords (required for SC_SUBM).
+ *                 SC_STRIDED layers do not look anything up in it (Section III-D builds the
+ *                 output side only): pass NULL and the build is self-contained - it then also
+ *                 resets *d_counts the way sc_hash_build does (n_in = n, status 0); pass the
+ *                 table of a preceding sc_hash_build and *d_counts is left as that call set it,
+ *                 including SC_EDUP, which only sc_hash_build can detect
  *   mode          SC_SUBM (stride must be 1, K odd, K <= SC_K_MAX) or SC_STRIDED (2 <= K <=
  *                 SC_K_MAX, 1 <= stride <= K, no padding: input p pairs with output cell q at
  *                 offset d iff p = q*stride + d; K == stride <= 4 is the down-sampling layer of

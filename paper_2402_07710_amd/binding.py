@@ -295,12 +295,14 @@ class LayerBuffers:
                 self.epoch = 1
             sc_grid_build(coords, self.table, self.grid_dims, self.epoch, self.counts, stream)
 
-    def kmap_build(self, coords, stream=None):
+    def kmap_build(self, coords, stream=None, standalone=False):
+        """standalone (strided layers): no location table is passed, the build starts the counts
+        block itself and repeated input coordinates go unnoticed."""
         if self.grid_dims is not None:
             sc_kmap_build_grid(coords, self.table, self.grid_dims, self.epoch, self.K, self.kmap, self.counts, stream)
             self.out_coords = coords
             return
-        sc_kmap_build(coords, self.table, self.K, self.stride, self.mode,
+        sc_kmap_build(coords, None if standalone else self.table, self.K, self.stride, self.mode,
                       None if self.mode == SC_SUBM else self.out_coords, self.kmap,
                       self.scratch, self.counts, stream)
         if self.mode == SC_SUBM:

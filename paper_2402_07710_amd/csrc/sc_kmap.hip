@@ -170,9 +170,16 @@ inline StridedScratch strided_scratch(void* p, int64_t n) {
 
 // One pass that prepares a strided build: output table <- empty, offset table <- -1.
 __global__ void __launch_bounds__(256)
-k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, int4* __restrict__ nbr16, int64_t nbr_vec) {
+k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, int4* __restrict__ nbr16, int64_t nbr_vec, sc_counts* reset,
+               int64_t n_in) {
     const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (reset != nullptr && blockIdx.x == 0) {       // a build without a location table starts the counts block itself
+        int32_t* w = reinterpret_cast<int32_t*>(reset);
+        for (int i = threadIdx.x; i < (int)(sizeof(sc_counts) / 4); i += blockDim.x) w[i] = 0;
+        __syncthreads();
+        if (threadIdx.x == 0) reset->n_in = n_in;
+    }
     const uint4 empty = make_uint4(0xffffffffu, 0xffffffffu, 0x7fffffffu, 0u);
     for (int64_t i = tid; i < (int64_t)cap; i += nthr) oslots[i] = empty;
     for (int64_t i = tid; i < nbr_vec; i += nthr) nbr16[i] = make_int4(-1, -1, -1, -1);
@@ -542,6 +549,9 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     h.magic = KMAP_MAGIC; h.K = K; h.stride = stride; h.mode = mode;
     h.n_in = n; h.n_out_bound = bound; h.tiles = L.tiles; h.mw = L.mw;
     if (n == 0) {
+        if (mode == SC_STRIDED && d_table == nullptr)
+            SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(1), dim3(256), 0, s, (uint4*)nullptr, (uint64_t)0, (int4*)nullptr,
+                      (int64_t)0, d_counts, (int64_t)0);
         SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap, h);
         SC_LAUNCH(KID_MISC, k_set_n_out, dim3(1), dim3(64), 0, s, d_counts, (int64_t)0);
         return SC_OK;
@@ -578,7 +588,8 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
             int64_t work = (int64_t)gcap > gvec ? (int64_t)gcap : gvec;
             unsigned fb = (unsigned)((work + 255) / 256);
             if (fb > 4096) fb = 4096;
-            SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, g.oslots, gcap, (int4*)nbr, gvec);
+            SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, g.oslots, gcap, (int4*)nbr, gvec,
+                      d_table == nullptr ? d_counts : (sc_counts*)nullptr, n);
         }
         const int64_t gblk = (nc + 1023) / 1024;
         const unsigned gg = (unsigned)((n + 255) / 256);
@@ -605,7 +616,8 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         int64_t work = (int64_t)cap > nbr_vec ? (int64_t)cap : nbr_vec;
         unsigned fb = (unsigned)((work + 255) / 256);
         if (fb > 4096) fb = 4096;
-        SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, sc_.oslots, cap, (int4*)nbr, nbr_vec);
+        SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, sc_.oslots, cap, (int4*)nbr, nbr_vec,
+                  d_table == nullptr ? d_counts : (sc_counts*)nullptr, n);
     }
     const int64_t nblk = (n + 1023) / 1024;
     const unsigned gb = (unsigned)((n + 255) / 256);
@@ -644,7 +656,7 @@ extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int strid
     unsigned fb = (unsigned)((nbr_vec + 255) / 256);
     if (fb > 4096) fb = 4096;
     SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, (uint4*)nullptr, (uint64_t)0, (int4*)inv_nbr,
-              nbr_vec);
+              nbr_vec, (sc_counts*)nullptr, (int64_t)0);
     int64_t items = L.tiles * L.K3;
     unsigned gb = (unsigned)((items + 3) / 4);
     if (gb > 4096) gb = 4096;

@@ -332,6 +332,23 @@ def test_strided_reports_duplicates():
     assert buf.read_counts(check=False).status == sc.SC_EDUP
 
 
+def test_strided_build_without_a_table_is_self_contained():
+    """sc_kmap_build(SC_STRIDED, d_table = NULL): same map as after sc_hash_build, and the build
+    starts the counts block itself (n_in, a clean status) whatever the block held before."""
+    say("strided standalone")
+    for K, s_, n in ((2, 2, 700), (3, 2, 300), (2, 2, 0)):
+        coords = synth.uniform_cells(n, 14, seed=K + n) if n else np.zeros((0, 4), np.int32)
+        buf = sc.LayerBuffers(n, K, s_, "strided", 32, 32, "f16", device=DEV)
+        d_coords = torch.from_numpy(coords).to(DEV).reshape(-1, 4)
+        buf.counts.fill_(0x7f)                                  # garbage, incl. a latched "error"
+        buf.kmap_build(d_coords, standalone=True)
+        h = buf.read_counts()
+        ref_km = oracle.kmap(coords, K, s_, "strided")
+        assert h.status == 0 and h.n_in == n and h.n_out == ref_km["n_out"] and h.n_pairs == ref_km["offset_start"][-1]
+        if n:
+            assert_maps_equal(exported_map(buf, h), buf.out_coords[:h.n_out].cpu().numpy(), ref_km, exact_order=True)
+
+
 def test_maps_are_reproducible_bit_for_bit():
     """The same input gives the same kernel-map bytes and the same output coordinates on every
     run (no dependence on thread timing)."""
