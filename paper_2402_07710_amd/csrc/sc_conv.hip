@@ -13,8 +13,6 @@
 // A layer of ~10^5 voxels is a few microseconds of matrix work, so what decides its time is how
 // many loads are in flight: the kernels below issue the offset-table reads of all K^3 offsets,
 // then all feature gathers, before the first multiply.
-#include <cstdlib>
-
 #include "sc_internal.h"
 
 namespace sc {
@@ -772,8 +770,7 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
     const size_t need = sc_conv_workspace_bytes(K, C_in, C_out, dtype_in);
     if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
     const int out_f32 = dtype_out == SC_F32;
-    static const bool force_any = getenv("SC_CONV_GENERIC") != nullptr;
-    if (!force_any) {
+    {
         bool handled = false;
         const MapSource ms{gmask, nbr, nullptr, nullptr, GridDims{0, 0, 0, 0}, 0u};
         const int rc = conv_16bit<0>(dtype_in, L.K3, C_in, C_out, tiles, s, d_feat_in, d_weight, d_workspace, d_feat_out,

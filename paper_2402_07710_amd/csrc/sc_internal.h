@@ -56,9 +56,9 @@ __host__ __device__ inline uint32_t probe_slot(uint64_t key, uint32_t t, uint32_
 // of the kernel map (every extra attempt is one more dependent round trip for the whole
 // wavefront), and memory is cheap: measured on ~53k voxels, whole layer with capacity >= 2n
 // 121 us, >= 4n 46 us, >= 8n 37 us, >= 16n 36.5 us (the fill then grows faster than the probes shrink).
-inline uint64_t hash_capacity(int64_t n) {
+inline uint64_t hash_capacity(int64_t n, uint64_t per_key = 8) {
     uint64_t cap = 1024;
-    while (cap < 8ull * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
+    while (cap < per_key * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
     return cap;
 }
 

@@ -151,9 +151,12 @@ struct StridedScratch {
     int32_t* block_prefix;   // [nblk]
     size_t bytes;
 };
-inline StridedScratch strided_scratch(void* p, int64_t n) {
+// n = entries of slot_of / flag bits (inputs, or candidates for K != stride); slots_per_key sizes
+// the output-cell table: 8 when every entry is a distinct cell at worst (K == stride: n cells),
+// 2 for candidate lists, whose n is a bound that real voxel sets stay far below
+inline StridedScratch strided_scratch(void* p, int64_t n, uint64_t slots_per_key = 8) {
     StridedScratch s;
-    const uint64_t cap = hash_capacity(n);
+    const uint64_t cap = hash_capacity(n, slots_per_key);
     const int64_t words = (n + 63) / 64, nblk = (n + 1023) / 1024;
     size_t off = 0;
     char* b = (char*)p;
@@ -305,6 +308,14 @@ k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
 // row and then by offset, and a cell's number is the rank of its lowest candidate id among all
 // cells' lowest ids: the same first-occurrence numbering as for K == stride, found with the same
 // flag / prefix kernels run over candidates instead of inputs.
+// offset table <- -1 for the tiles that hold the counts->n_out output rows
+__global__ void __launch_bounds__(256)
+k_fill_rows(int4* __restrict__ nbr16, int K3, const sc_counts* __restrict__ counts) {
+    const int64_t vec = (counts->n_out + TILE - 1) / TILE * K3 * (TILE / 4);
+    const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vec; i += nthr) nbr16[i] = make_int4(-1, -1, -1, -1);
+}
+
 template <typename F>
 __device__ inline void for_each_candidate(const int4 c, int K, int s, F&& f) {
     int j = 0;
@@ -524,7 +535,9 @@ extern "C" size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode) {
 extern "C" size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode) {
     if (!kmap_args_ok(n, K, stride, mode)) return 0;
     if (mode == SC_SUBM) return 256;
-    return strided_scratch(nullptr, sc_out_bound(n, K, stride, mode)).bytes;    // one entry per candidate
+    if (mode == SC_STRIDED && !strided_fast(K, stride))
+        return strided_scratch(nullptr, sc_out_bound(n, K, stride, mode), 2).bytes;    // one entry per candidate
+    return strided_scratch(nullptr, n).bytes;
 }
 
 extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
@@ -581,14 +594,15 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         // strided, general K and stride: the same pipeline over candidates (input, offset)
         const int maxc = strided_maxc(K, stride);
         const int64_t nc = n * maxc;
-        StridedScratch g = strided_scratch(d_scratch, nc);
+        StridedScratch g = strided_scratch(d_scratch, nc, 2);
         const uint64_t gcap = (uint64_t)g.omask + 1;
         const int64_t gvec = (int64_t)((L.bytes - L.off_nbr) / 16);
         {
-            int64_t work = (int64_t)gcap > gvec ? (int64_t)gcap : gvec;
-            unsigned fb = (unsigned)((work + 255) / 256);
+            // the offset table is filled further down, once the number of output rows is known: the
+            // bound is ceil(K/s)^3 rows per input, real sets need about one
+            unsigned fb = (unsigned)((gcap + 255) / 256);
             if (fb > 4096) fb = 4096;
-            SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, g.oslots, gcap, (int4*)nbr, gvec,
+            SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, g.oslots, gcap, (int4*)nbr, (int64_t)0,
                       d_table == nullptr ? d_counts : (sc_counts*)nullptr, n);
         }
         const int64_t gblk = (nc + 1023) / 1024;
@@ -599,6 +613,11 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
                   (const int32_t*)g.slot_of, (const uint4*)g.oslots, g.flagword, g.word_prefix, g.block_sum);
         SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)g.block_sum,
                   g.block_prefix, gblk, d_counts);
+        {
+            unsigned fb = (unsigned)((gvec + 255) / 256);
+            if (fb > 2048) fb = 2048;
+            SC_LAUNCH(KID_FILL_I32, k_fill_rows, dim3(fb), dim3(256), 0, s, (int4*)nbr, L.K3, (const sc_counts*)d_counts);
+        }
         SC_LAUNCH(KID_STRIDED_PAIRS, k_gstrided_pairs, dim3(gg), dim3(256), 0, s, (const int4*)d_coords, n, K, stride,
                   maxc, (const int32_t*)g.slot_of, (const uint4*)g.oslots, (const uint64_t*)g.flagword,
                   (const int32_t*)g.word_prefix, (const int32_t*)g.block_prefix, nbr, (int4*)d_out_coords,
