@@ -316,8 +316,11 @@ def main() -> int:
                             "per_step_us": round(per_step_us[name], 3)}
         if ab:
             per_kernel[name]["hbm_gbs_algorithmic"] = round(ab / (kernels[name]["avg_us"] * 1e-6) / 1e9, 1)
+            per_kernel[name]["frac_of_hbm_peak"] = round(ab / (kernels[name]["avg_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)
         if name in ("k_conv_mfma", "k_conv_f32"):
             per_kernel[name]["tflops_active"] = round(flops / (kernels[name]["avg_us"] * 1e-6) / 1e12, 2)
+            if name == "k_conv_mfma":
+                per_kernel[name]["frac_of_mfma_peak"] = round(flops / (kernels[name]["avg_us"] * 1e-6) / 1e12 / PEAK_MFMA_TFLOPS, 4)
 
     out = {
         "metric": "effective TFLOP/s over active MACs, whole layer incl. kernel map (hash + kmap + conv)",
