@@ -288,7 +288,7 @@ def main() -> int:
     dominant = max(per_step_us, key=per_step_us.get)
     launches_per_step = prof[dominant][0] / args.steps
     avg_s = kernels[dominant]["avg_us"] * 1e-6
-    st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=sc.sc_hash_bytes(N) // 16, C_in=C_in, C_out=C_out,
+    st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=(sc.sc_hash_bytes(N) - 256) // 16, C_in=C_in, C_out=C_out,
               elem_bytes=d_feat.element_size())
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")

@@ -23,9 +23,10 @@
  *     are detected on the host before anything is enqueued.  Data-dependent errors (duplicate
  *     or out-of-domain coordinates, table overflow) are latched by the kernels into
  *     sc_counts.status on the device and reported by sc_counts_read.
- *   - Coordinate domain: 0 <= b, x, y, z <= SC_COORD_MAX (16 bits each; the all-ones key is
- *     reserved as the empty marker).  1 <= n <= SC_N_MAX rows (n = 0 is accepted and yields
- *     empty results).  Neighbour probes that leave the domain simply miss; nothing wraps.
+ *   - Coordinate domain: 0 <= b <= SC_BATCH_MAX, 0 <= x, y, z <= SC_COORD_MAX (8 + 3 x 16 bits
+ *     of a 64-bit key whose top byte holds the epoch of the build).  1 <= n <= SC_N_MAX rows
+ *     (n = 0 is accepted and yields empty results).  Neighbour probes that leave the domain
+ *     simply miss; nothing wraps.
  *   - Kernel offsets d in {0..K-1}^3 are numbered k = dX*K^2 + dY*K + dZ (Section III-B eq. 5).
  *     A pair (in = i, out = o) belongs to offset k iff p_i = q_o*stride + d_k - pad, batch
  *     equal, with pad = (K-1)/2 for submanifold layers and 0 for strided ones (the direction
@@ -64,6 +65,8 @@ extern "C" {
 #define SC_BF16      2
 
 #define SC_COORD_MAX 65534
+#define SC_BATCH_MAX 255
+#define SC_HASH_EPOCH_MAX 254      /* epochs of sc_hash_rebuild: 1..254 */
 #define SC_N_MAX     67108864LL   /* 2^26 rows: kernel-map entries pack (row, 6-bit slot) in 32 bits */
 #define SC_K_MAX     7            /* K^3 <= 343 */
 
@@ -80,15 +83,34 @@ typedef struct sc_counts {
  * library uses an open-addressing hash table keyed on the packed 64-bit (b,x,y,z)) ---------- */
 
 /* Bytes of the table for n keys: 16 bytes per slot, capacity = power of two >= 8n and >= 1024
- * slots, so the load factor stays <= 1/8. */
+ * slots, so the load factor stays <= 1/8, plus a 256-byte header. */
 size_t sc_hash_bytes(int64_t n);
 
 /* Build the table coordinate -> row index over d_coords [n][4] (b,x,y,z).  Also resets
  * *d_counts (n_in = n, everything else 0).  Latches SC_ERANGE / SC_EDUP into d_counts->status.
- * d_table: table_bytes >= sc_hash_bytes(n) bytes, fully overwritten. */
+ * d_table: table_bytes >= sc_hash_bytes(n) bytes, fully overwritten (one pass that fills every
+ * slot, then the inserts). */
 int sc_hash_build(const int32_t* d_coords, int64_t n,
                   void* d_table, size_t table_bytes,
                   sc_counts* d_counts, void* stream);
+
+/* Build again into a table that sc_hash_build has initialised, without the filling pass: stored
+ * keys carry the epoch of their build, and whatever another epoch left in a slot counts as
+ * free.  `epoch` is any value in 1..SC_HASH_EPOCH_MAX not used on this table since its last
+ * sc_hash_build (a counter; call sc_hash_build again when it runs out).  table_bytes >=
+ * sc_hash_bytes(n) as for sc_hash_build.  n may change from build to build: the table keeps
+ * the capacity it was last filled with, and a build of more than a quarter of that many rows
+ * is refused with SC_ECAP.  Resets *d_counts like sc_hash_build.  SC_ERANGE / SC_EDUP /
+ * SC_ECAP of such a build are kept in the table's header and latched into d_counts->status by
+ * the next sc_kmap_build that is given this table; sc_hash_lookup alone does not report them
+ * (a duplicated coordinate maps to one of its rows, a coordinate outside the domain is
+ * absent).  Tables above 16 MiB are filled all the same, with the capacity for n (measured
+ * faster there: the fill leaves the table in the last-level cache for the probes that
+ * follow), and then report like sc_hash_build.
+ * SC_EINVAL if epoch is outside 1..SC_HASH_EPOCH_MAX. */
+int sc_hash_rebuild(const int32_t* d_coords, int64_t n,
+                    void* d_table, size_t table_bytes, int epoch,
+                    sc_counts* d_counts, void* stream);
 
 /* ---- dense location table (Section III-C.1 offers both forms: a "large array" indexed by the
  * linearised coordinate, eq. 6, which the paper prefers when the domain is confined, or a hash

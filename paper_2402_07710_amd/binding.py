@@ -18,6 +18,7 @@ SC_OK, SC_EINVAL, SC_ERANGE, SC_EDUP, SC_ECAP, SC_EHIP, SC_EFULL = 0, -1, -2, -3
 SC_SUBM, SC_STRIDED, SC_INVERSE = 0, 1, 2
 SC_F32, SC_F16, SC_BF16 = 0, 1, 2
 SC_COORD_MAX, SC_N_MAX, SC_K_MAX = 65534, 1 << 26, 7
+SC_BATCH_MAX, SC_HASH_EPOCH_MAX = 255, 254
 MODES = {"subm": SC_SUBM, "strided": SC_STRIDED, "inverse": SC_INVERSE,
          SC_SUBM: SC_SUBM, SC_STRIDED: SC_STRIDED, SC_INVERSE: SC_INVERSE}
 DTYPES = {"f32": SC_F32, "f16": SC_F16, "bf16": SC_BF16,
@@ -25,7 +26,7 @@ DTYPES = {"f32": SC_F32, "f16": SC_F16, "bf16": SC_BF16,
 TORCH_DTYPES = {SC_F32: torch.float32, SC_F16: torch.float16, SC_BF16: torch.bfloat16}
 
 # every symbol include/sc.h declares
-SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
+SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_rebuild", "sc_hash_lookup", "sc_out_bound", "sc_kmap_bytes",
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
            "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid",
@@ -68,6 +69,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     sig = {
         "sc_hash_bytes": (sz, [i64]),
         "sc_hash_build": (i32, [vp, i64, vp, sz, vp, vp]),
+        "sc_hash_rebuild": (i32, [vp, i64, vp, sz, i32, vp, vp]),
         "sc_hash_lookup": (i32, [vp, i64, vp, i64, vp, vp]),
         "sc_out_bound": (i64, [i64, i32, i32, i32]),
         "sc_kmap_bytes": (sz, [i64, i32, i32, i32]),
@@ -147,6 +149,13 @@ def sc_hash_build(coords, table, counts, stream=None):
     n = coords.shape[0]
     _check(load().sc_hash_build(_ptr(coords), n, _ptr(table), table.numel() * table.element_size(),
                                 _ptr(counts), _stream(stream)), "sc_hash_build")
+
+
+def sc_hash_rebuild(coords, table, epoch, counts, stream=None):
+    """Build again, without the filling pass, into a table that sc_hash_build initialised (same n)."""
+    n = coords.shape[0]
+    _check(load().sc_hash_rebuild(_ptr(coords), n, _ptr(table), table.numel() * table.element_size(), epoch,
+                                  _ptr(counts), _stream(stream)), "sc_hash_rebuild")
 
 
 def sc_hash_lookup(table, n_table, query, rows, stream=None):
@@ -268,6 +277,7 @@ class LayerBuffers:
             raise ScError(SC_EINVAL, "sc_out_bound")
         u8 = dict(dtype=torch.uint8, device=device)
         self.grid_dims, self.epoch = grid_dims, 0
+        self._hash_n = None          # rows of the sc_hash_build that initialised the hash table
         if grid_dims is None:
             self.table = torch.empty(max(sc_hash_bytes(n), 16), **u8)
         else:
@@ -287,7 +297,13 @@ class LayerBuffers:
     def hash_build(self, coords, stream=None):
         """Location table over `coords`: the hash table, or the dense array if grid_dims was given."""
         if self.grid_dims is None:
-            sc_hash_build(coords, self.table, self.counts, stream)
+            # the first build fills the table; later ones of the same size only move to a new epoch
+            if self._hash_n == coords.shape[0] and self.epoch < SC_HASH_EPOCH_MAX:
+                self.epoch += 1
+                sc_hash_rebuild(coords, self.table, self.epoch, self.counts, stream)
+            else:
+                self._hash_n, self.epoch = coords.shape[0], 0
+                sc_hash_build(coords, self.table, self.counts, stream)
         else:
             self.epoch += 1
             if self.epoch >= 1 << 32:

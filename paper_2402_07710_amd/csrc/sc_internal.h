@@ -13,20 +13,25 @@ namespace sc {
 
 constexpr int WAVE = 64;                      // CDNA wavefront
 constexpr int TILE = 64;                      // output rows per kernel-map tile (= one wavefront)
-constexpr uint64_t KEY_EMPTY = ~0ull;         // (65535,65535,65535,65535): outside the domain
+constexpr uint64_t KEY_EMPTY = ~0ull;         // epoch field 0xff: no build ever uses it
 constexpr uint32_t KMAP_MAGIC = 0x70614d6bu;
 
 // ---- coordinate keys ------------------------------------------------------------------------
 // The paper linearises (x,y,z) into one dense-array index (Section III-C.1 eq. 6); the batch
-// index is part of the coordinate (Section II-A), so here all four 16-bit fields are packed
-// into one 64-bit key instead.
+// index is part of the coordinate (Section II-A), so here the batch (8 bits) and the three 16-bit
+// coordinates are packed into the low 56 bits of one 64-bit word.  The top 8 bits of a stored
+// word carry the epoch of the build that wrote it: a slot whose epoch is not the table's current
+// one is free, whatever else it holds, so a table that is built again needs no refill.
+constexpr int KEY_EPOCH_SHIFT = 56;
 __host__ __device__ inline uint64_t pack_key(int b, int x, int y, int z) {
     return ((uint64_t)(uint32_t)b << 48) | ((uint64_t)(uint32_t)x << 32) |
            ((uint64_t)(uint32_t)y << 16) | (uint64_t)(uint32_t)z;
 }
+__host__ __device__ inline uint64_t epoch_tag(uint32_t epoch) { return (uint64_t)epoch << KEY_EPOCH_SHIFT; }
+__host__ __device__ inline bool same_epoch(uint64_t word, uint64_t tag) { return ((word ^ tag) >> KEY_EPOCH_SHIFT) == 0; }
 __host__ __device__ inline bool in_domain(int v) { return (unsigned)v <= (unsigned)SC_COORD_MAX; }
 __host__ __device__ inline bool in_domain4(int b, int x, int y, int z) {
-    return in_domain(b) && in_domain(x) && in_domain(y) && in_domain(z);
+    return (unsigned)b <= (unsigned)SC_BATCH_MAX && in_domain(x) && in_domain(y) && in_domain(z);
 }
 
 // Probe sequence of a key.  The table is cut into regions of 64 slots; a 4x4x4 block of cells
@@ -62,27 +67,40 @@ inline uint64_t hash_capacity(int64_t n, uint64_t per_key = 8) {
     return cap;
 }
 
-// One 16-byte slot per key: {key (8 bytes), value (4), unused (4)}, so a probe is one 16-byte
-// load that brings the key and the row index together.
+// One 16-byte slot per key: {epoch | key (8 bytes), value (4), unused (4)}, so a probe is one
+// 16-byte load that brings the key and the row index together.  A 256-byte header precedes the
+// slots: the table's capacity (fixed by the build that filled it), the epoch of the last build,
+// and the first error a build without a fill came across (tagged with its epoch, so it needs no
+// reset: stale tags never match).
+struct TableHeader {
+    uint32_t mask;            // capacity - 1
+    uint32_t epoch;           // of the last build (0 after sc_hash_build)
+    uint32_t err_tag;         // (epoch << 8) | -status of a build with epoch >= 1, or 0
+    uint32_t pad[61];
+};
+static_assert(sizeof(TableHeader) == 256, "table header");
 struct HashTable {            // view of a caller-owned table buffer
-    uint4* slots;             // [cap]: x,y = key (low, high), z = value
-    uint32_t mask;            // cap - 1
+    TableHeader* hdr;
+    uint4* slots;             // [cap]: x,y = epoch | key (low, high), z = value
+    uint32_t mask;            // cap - 1 of a table for n keys (what the header of a fresh table says)
 };
 inline HashTable table_view(void* p, int64_t n) {
     HashTable t;
-    t.slots = (uint4*)p;
+    t.hdr = (TableHeader*)p;
+    t.slots = (uint4*)((char*)p + sizeof(TableHeader));
     t.mask = (uint32_t)(hash_capacity(n) - 1);
     return t;
 }
 __host__ __device__ inline uint64_t slot_key(const uint4& s) { return (uint64_t)s.x | ((uint64_t)s.y << 32); }
 
-// Probe for `key`; returns the stored value or -1.  The table is never full.
-__device__ inline int32_t table_find(const uint4* __restrict__ slots, uint32_t mask, uint64_t key) {
+// Probe for `key` among the slots of the epoch in `tag`; returns the stored value or -1.  The
+// table is never full.
+__device__ inline int32_t table_find(const uint4* __restrict__ slots, uint32_t mask, uint64_t key, uint64_t tag) {
     for (uint32_t t = 0; t <= mask + REHASH_MAX; ++t) {
         const uint4 s = slots[probe_slot(key, t, mask)];
         const uint64_t cur = slot_key(s);
-        if (cur == key) return (int32_t)s.z;
-        if (cur == KEY_EMPTY) return -1;
+        if (cur == (key | tag)) return (int32_t)s.z;
+        if (!same_epoch(cur, tag)) return -1;
     }
     return -1;
 }
@@ -92,7 +110,13 @@ __device__ inline void latch_status(sc_counts* counts, int code) {
 }
 
 // every slot <- {EMPTY, val_init}; optionally *counts reset (defined in sc_hash.hip)
-int launch_table_fill(uint4* slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in, hipStream_t s);
+int launch_table_fill(uint4* slots, uint64_t cap, int32_t val_init, sc_counts* counts, int64_t n_in, hipStream_t s,
+                      TableHeader* th = nullptr, uint32_t epoch = 0);
+// what a later build on `table` has to report: the error of an epoch >= 1 build, if any
+__device__ inline void fold_table_error(const TableHeader* th, sc_counts* counts) {
+    const uint32_t e = th->epoch, tag = th->err_tag;
+    if (e != 0 && (tag >> 8) == e) latch_status(counts, -(int)(tag & 0xffu));
+}
 
 // ---- dense location table (sc_grid.hip) -------------------------------------------------------
 // One 8-byte cell {row (low 32 bits), epoch (high 32 bits)} per site of the box, z fastest.

@@ -38,9 +38,9 @@ k_set_n_out(sc_counts* counts, int64_t n_out) {
 // 256-byte line of the tile and votes (ballot) on which 16-row groups have a neighbour.
 template <int K, int WPT, int CH, int AT>
 __global__ void __launch_bounds__(64 * WPT)
-k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict__ slots, uint32_t mask,
-            uint32_t* __restrict__ gmask, int32_t* __restrict__ nbr, sc_counts* counts, KmapHeader* hdr,
-            KmapHeader hdr_value) {
+k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict__ slots,
+            const TableHeader* __restrict__ th, uint32_t* __restrict__ gmask, int32_t* __restrict__ nbr,
+            sc_counts* counts, KmapHeader* hdr, KmapHeader hdr_value) {
     constexpr int K3 = K * K * K, pad = (K - 1) / 2, centre = (K3 - 1) / 2;
     constexpr int PER_PASS = WPT * CH;
     constexpr int PASSES = (K3 + PER_PASS - 1) / PER_PASS;
@@ -56,9 +56,12 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
     const bool valid = row < n;
     int4 c = make_int4(0, 0, 0, 0);
     if (valid) c = coords[row];
+    const uint32_t mask = th->mask;
+    const uint64_t tag = epoch_tag(th->epoch);       // slots of other epochs are free
     if (tile == 0 && threadIdx.x == 0) {
         counts->n_out = n;
         *hdr = hdr_value;
+        fold_table_error(th, counts);
     }
     __syncthreads();
 
@@ -114,8 +117,8 @@ k_kmap_subm(const int4* __restrict__ coords, int64_t n, const uint4* __restrict_
                     for (int a = 0; a < AT; ++a) {
                         if (pending & (1u << u)) {
                             const uint64_t cur = (uint64_t)got[u][a].x | ((uint64_t)got[u][a].y << 32);
-                            if (cur == key) { found[u] = (int32_t)got[u][a].z; pending &= ~(1u << u); }
-                            else if (cur == KEY_EMPTY) pending &= ~(1u << u);
+                            if (cur == (key | tag)) { found[u] = (int32_t)got[u][a].z; pending &= ~(1u << u); }
+                            else if (!same_epoch(cur, tag)) pending &= ~(1u << u);
                         }
                     }
                 }
@@ -173,16 +176,18 @@ inline StridedScratch strided_scratch(void* p, int64_t n, uint64_t slots_per_key
 
 // One pass that prepares a strided build: output table <- empty, offset table <- -1.
 __global__ void __launch_bounds__(256)
-k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, int4* __restrict__ nbr16, int64_t nbr_vec, sc_counts* reset,
-               int64_t n_in) {
+k_strided_fill(uint4* __restrict__ oslots, uint64_t cap, int4* __restrict__ nbr16, int64_t nbr_vec, sc_counts* counts,
+               int reset, int64_t n_in, const TableHeader* th) {
     const int64_t nthr = (int64_t)gridDim.x * blockDim.x;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (reset != nullptr && blockIdx.x == 0) {       // a build without a location table starts the counts block itself
-        int32_t* w = reinterpret_cast<int32_t*>(reset);
+    if (reset && blockIdx.x == 0) {                  // a build without a location table starts the counts block itself
+        int32_t* w = reinterpret_cast<int32_t*>(counts);
         for (int i = threadIdx.x; i < (int)(sizeof(sc_counts) / 4); i += blockDim.x) w[i] = 0;
         __syncthreads();
-        if (threadIdx.x == 0) reset->n_in = n_in;
+        if (threadIdx.x == 0) counts->n_in = n_in;
     }
+    // after a location-table build that could not report into the counts block, report for it
+    if (th != nullptr && tid == 0) fold_table_error(th, counts);
     const uint4 empty = make_uint4(0xffffffffu, 0xffffffffu, 0x7fffffffu, 0u);
     for (int64_t i = tid; i < (int64_t)cap; i += nthr) oslots[i] = empty;
     for (int64_t i = tid; i < nbr_vec; i += nthr) nbr16[i] = make_int4(-1, -1, -1, -1);
@@ -564,7 +569,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     if (n == 0) {
         if (mode == SC_STRIDED && d_table == nullptr)
             SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(1), dim3(256), 0, s, (uint4*)nullptr, (uint64_t)0, (int4*)nullptr,
-                      (int64_t)0, d_counts, (int64_t)0);
+                      (int64_t)0, d_counts, 1, (int64_t)0, (const TableHeader*)nullptr);
         SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap, h);
         SC_LAUNCH(KID_MISC, k_set_n_out, dim3(1), dim3(64), 0, s, d_counts, (int64_t)0);
         return SC_OK;
@@ -574,7 +579,8 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         HashTable t = table_view(const_cast<void*>(d_table), n);
 #define SC_SUBM_LAUNCH(KV, WPT, CH, AT)                                                                           \
     SC_LAUNCH(KID_KMAP_SUBM, (k_kmap_subm<KV, WPT, CH, AT>), dim3(xcd_grid(L.tiles)), dim3(64 * WPT), 0, s,      \
-              (const int4*)d_coords, n, (const uint4*)t.slots, t.mask, gmask, nbr, d_counts, (KmapHeader*)d_kmap, h)
+              (const int4*)d_coords, n, (const uint4*)t.slots, (const TableHeader*)t.hdr, gmask, nbr, d_counts,          \
+              (KmapHeader*)d_kmap, h)
         switch (K) {
             case 1: SC_SUBM_LAUNCH(1, 1, 1, 1); break;
             case 3: SC_SUBM_LAUNCH(3, 8, 4, 1); break;
@@ -590,6 +596,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         return SC_OK;
     }
 
+    const TableHeader* table_hdr = (const TableHeader*)d_table;
     if (!strided_fast(K, stride)) {
         // strided, general K and stride: the same pipeline over candidates (input, offset)
         const int maxc = strided_maxc(K, stride);
@@ -603,7 +610,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
             unsigned fb = (unsigned)((gcap + 255) / 256);
             if (fb > 4096) fb = 4096;
             SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, g.oslots, gcap, (int4*)nbr, (int64_t)0,
-                      d_table == nullptr ? d_counts : (sc_counts*)nullptr, n);
+                      d_counts, d_table == nullptr ? 1 : 0, n, table_hdr);
         }
         const int64_t gblk = (nc + 1023) / 1024;
         const unsigned gg = (unsigned)((n + 255) / 256);
@@ -636,7 +643,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
         unsigned fb = (unsigned)((work + 255) / 256);
         if (fb > 4096) fb = 4096;
         SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, sc_.oslots, cap, (int4*)nbr, nbr_vec,
-                  d_table == nullptr ? d_counts : (sc_counts*)nullptr, n);
+                  d_counts, d_table == nullptr ? 1 : 0, n, table_hdr);
     }
     const int64_t nblk = (n + 1023) / 1024;
     const unsigned gb = (unsigned)((n + 255) / 256);
@@ -675,7 +682,7 @@ extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int strid
     unsigned fb = (unsigned)((nbr_vec + 255) / 256);
     if (fb > 4096) fb = 4096;
     SC_LAUNCH(KID_FILL_I32, k_strided_fill, dim3(fb), dim3(256), 0, s, (uint4*)nullptr, (uint64_t)0, (int4*)inv_nbr,
-              nbr_vec, (sc_counts*)nullptr, (int64_t)0);
+              nbr_vec, (sc_counts*)nullptr, 0, (int64_t)0, (const TableHeader*)nullptr);
     int64_t items = L.tiles * L.K3;
     unsigned gb = (unsigned)((items + 3) / 4);
     if (gb > 4096) gb = 4096;

@@ -38,11 +38,11 @@ def test_counts_struct_layout():
 
 def test_size_queries(lib):
     # 16-byte slots, capacity = power of two >= 4n (at least 1024)
-    assert lib.sc_hash_bytes(0) == 1024 * 16
-    assert lib.sc_hash_bytes(128) == 1024 * 16
-    assert lib.sc_hash_bytes(129) == 2048 * 16
-    assert lib.sc_hash_bytes(1000) == 8192 * 16
-    assert lib.sc_hash_bytes(1025) == 16384 * 16
+    assert lib.sc_hash_bytes(0) == 1024 * 16 + 256
+    assert lib.sc_hash_bytes(128) == 1024 * 16 + 256
+    assert lib.sc_hash_bytes(129) == 2048 * 16 + 256
+    assert lib.sc_hash_bytes(1000) == 8192 * 16 + 256
+    assert lib.sc_hash_bytes(1025) == 16384 * 16 + 256
     assert lib.sc_hash_bytes(-1) == 0
     assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
     assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
@@ -76,6 +76,10 @@ def test_host_side_argument_errors(lib):
     assert lib.sc_hash_build(None, -1, 16, 0, 16, None) == binding.SC_EINVAL
     assert lib.sc_hash_build(16, 10, 32, 8, 48, None) == binding.SC_ECAP
     assert lib.sc_hash_build(17, 10, 32, 1 << 20, 48, None) == binding.SC_EINVAL      # misaligned
+    for epoch in (0, -1, binding.SC_HASH_EPOCH_MAX + 1):
+        assert lib.sc_hash_rebuild(16, 10, 32, 1 << 20, epoch, 48, None) == binding.SC_EINVAL
+    assert lib.sc_hash_rebuild(16, 10, 32, 8, 1, 48, None) == binding.SC_ECAP
+    assert lib.sc_hash_rebuild(None, 10, 32, 1 << 20, 1, 48, None) == binding.SC_EINVAL
     assert lib.sc_kmap_build(16, 10, 32, 2, 1, binding.SC_SUBM, None, 64, 1 << 20, None, 0, 80, None) == binding.SC_EINVAL
     assert lib.sc_kmap_build(16, 10, 32, 3, 1, binding.SC_SUBM, None, 64, 8, None, 0, 80, None) == binding.SC_ECAP
     assert lib.sc_kmap_build(16, 10, None, 3, 1, binding.SC_SUBM, None, 64, 1 << 20, None, 0, 80, None) == binding.SC_EINVAL

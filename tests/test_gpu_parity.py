@@ -137,6 +137,145 @@ def test_hash_reports_duplicates_and_range():
     assert sc.sc_counts_read(counts).status == 0
 
 
+
+def fresh_table(n):
+    table = torch.empty(sc.sc_hash_bytes(n), dtype=torch.uint8, device=DEV)
+    counts = torch.zeros(sc.COUNTS_BYTES + 8, dtype=torch.uint8, device=DEV)
+    return table, counts
+
+
+def lookup_np(table, n, query):
+    rows = torch.empty(len(query), dtype=torch.int32, device=DEV)
+    sc.sc_hash_lookup(table, n, torch.from_numpy(np.ascontiguousarray(query, dtype=np.int32)).to(DEV), rows)
+    return rows.cpu().numpy()
+
+
+def test_hash_rebuild_sees_only_the_last_build():
+    """A table that is built again without the filling pass: keys of earlier builds are gone,
+    also when the new set overlaps the old one or reuses its slots."""
+    say("hash rebuild epochs")
+    n = 3000
+    sets = [synth.uniform_cells(n, 24, seed=s) for s in (1, 2, 3)]
+    sets.append(sets[0][::-1].copy())                      # an old set again, rows renumbered
+    sets.append(np.roll(sets[1], 7, axis=0))
+    table, counts = fresh_table(n)
+    everything = np.unique(np.concatenate(sets), axis=0)
+    for epoch, coords in enumerate(sets):
+        d = torch.from_numpy(coords).to(DEV)
+        if epoch == 0:
+            sc.sc_hash_build(d, table, counts)
+        else:
+            sc.sc_hash_rebuild(d, table, epoch, counts)
+        h = sc.sc_counts_read(counts)
+        assert h.n_in == n and h.status == 0
+        assert np.array_equal(lookup_np(table, n, coords), np.arange(n))
+        want = {tuple(c): i for i, c in enumerate(coords.tolist())}
+        got = lookup_np(table, n, everything)
+        assert np.array_equal(got, np.array([want.get(tuple(c), -1) for c in everything.tolist()]))
+    # epochs need not be consecutive, only unused
+    coords = synth.uniform_cells(n, 24, seed=9)
+    sc.sc_hash_rebuild(torch.from_numpy(coords).to(DEV), table, sc.SC_HASH_EPOCH_MAX, counts)
+    assert np.array_equal(lookup_np(table, n, coords), np.arange(n))
+    got = lookup_np(table, n, everything)
+    want = {tuple(c): i for i, c in enumerate(coords.tolist())}
+    assert np.array_equal(got, np.array([want.get(tuple(c), -1) for c in everything.tolist()]))
+
+
+def test_hash_rebuild_with_fewer_and_more_rows():
+    """The capacity is the one the table was filled with, whatever n later builds bring."""
+    say("hash rebuild sizes")
+    n0 = 2000
+    table, counts = fresh_table(n0)
+    sc.sc_hash_build(torch.from_numpy(synth.uniform_cells(n0, 20, seed=1)).to(DEV), table, counts)
+    for epoch, n in enumerate([1, 130, 1999, 2000, 0, 700], start=1):
+        coords = synth.uniform_cells(n, 20, seed=10 + epoch) if n else np.zeros((0, 4), np.int32)
+        d = torch.from_numpy(coords).to(DEV).reshape(-1, 4)
+        sc.sc_hash_rebuild(d, table, epoch, counts)
+        h = sc.sc_counts_read(counts)
+        assert h.n_in == n and h.status == 0
+        if n:
+            assert np.array_equal(lookup_np(table, n0, coords), np.arange(n))
+        probe = synth.uniform_cells(500, 20, seed=77)
+        want = {tuple(c): i for i, c in enumerate(coords.tolist())}
+        assert np.array_equal(lookup_np(table, n0, probe), np.array([want.get(tuple(c), -1) for c in probe.tolist()]))
+
+
+def test_hash_rebuild_layers_match_oracle_across_the_epoch_wrap():
+    """Layer after layer on one set of buffers: more builds than there are epochs, so the table
+    is refilled on the way; every layer must give the oracle's map and output."""
+    say("hash rebuild layers")
+    n, C = 700, 32
+    buf = sc.LayerBuffers(n, 3, 1, "subm", C, C, "f16", device=DEV)
+    cases = []
+    for s in range(3):
+        coords = synth.uniform_cells(n, 14, seed=40 + s)
+        feat = synth.features(n, C, "f16", s)
+        weight = synth.weights(27, C, C, "f16", s)
+        km = oracle.kmap(coords, 3, 1, "subm")
+        cases.append((torch.from_numpy(coords).to(DEV), to_dev(feat, "f16"), to_dev(weight, "f16"), km,
+                      oracle.conv(feat, weight, km)))
+    seen_epochs = set()
+    for it in range(sc.SC_HASH_EPOCH_MAX + 8):
+        d_coords, d_feat, d_w, km, ref = cases[it % 3]
+        buf.layer(d_coords, d_feat, d_w)
+        seen_epochs.add(buf.epoch)
+        if it < 6 or it > sc.SC_HASH_EPOCH_MAX - 3:
+            h = buf.read_counts()
+            assert h.status == 0 and h.n_pairs == km["offset_start"][-1]
+            assert_maps_equal(exported_map(buf, h), buf.out_coords.cpu().numpy(), km, exact_order=True)
+        else:
+            assert buf.read_counts(with_pairs=False).status == 0
+        assert rel_err(buf.feat_out[:n].to(torch.float64).cpu().numpy(), ref) <= TOL["f16"]
+    assert seen_epochs == set(range(sc.SC_HASH_EPOCH_MAX + 1))
+
+
+def test_hash_rebuild_errors_surface_at_the_map_build():
+    say("hash rebuild errors")
+    n = 500
+    coords = synth.uniform_cells(n, 16, seed=1)
+    d_good = torch.from_numpy(coords).to(DEV)
+    dup = coords.copy()
+    dup[400] = dup[17]
+    bad = coords.copy()
+    bad[3, 0] = sc.SC_BATCH_MAX + 1
+    for mode, K, s in (("subm", 3, 1), ("strided", 2, 2), ("strided", 3, 2)):
+        buf = sc.LayerBuffers(n, K, s, mode, 32, 32, "f16", device=DEV)
+        buf.hash_build(d_good)                                   # fills the table (epoch 0)
+        buf.kmap_build(d_good)
+        assert buf.read_counts(check=False).status == 0
+        for wrong, code in ((dup, sc.SC_EDUP), (bad, sc.SC_ERANGE)):
+            d = torch.from_numpy(wrong).to(DEV)
+            buf.hash_build(d)                                    # a rebuild: the error waits in the table
+            assert buf.epoch >= 1
+            buf.kmap_build(d)
+            assert buf.read_counts(check=False, with_pairs=False).status == code
+            buf.hash_build(d_good)                               # and does not outlive its build
+            buf.kmap_build(d_good)
+            assert buf.read_counts(check=False).status == 0
+    # more rows than the table was filled for: refused by the build, reported like the others
+    table = torch.empty(sc.sc_hash_bytes(4 * n), dtype=torch.uint8, device=DEV)
+    counts = torch.zeros(sc.COUNTS_BYTES + 8, dtype=torch.uint8, device=DEV)
+    sc.sc_hash_build(d_good[:100].contiguous(), table, counts)           # capacity 1024
+    big = torch.from_numpy(synth.uniform_cells(300, 16, seed=5)).to(DEV)
+    sc.sc_hash_rebuild(big, table, 1, counts)
+    kmap = torch.empty(sc.sc_kmap_bytes(300, 3, 1, "subm"), dtype=torch.uint8, device=DEV)
+    sc.sc_kmap_build(big, table, 3, 1, "subm", None, kmap, None, counts)
+    assert sc.sc_counts_read(counts, check=False).status == sc.SC_ECAP
+
+
+def test_hash_batch_index_range():
+    say("hash batch range")
+    coords = synth.uniform_cells(200, 8, seed=3)
+    coords[:, 0] = np.arange(200) % (sc.SC_BATCH_MAX + 1)
+    table, counts = fresh_table(200)
+    sc.sc_hash_build(torch.from_numpy(coords).to(DEV), table, counts)
+    assert sc.sc_counts_read(counts).status == 0
+    assert np.array_equal(lookup_np(table, 200, coords), np.arange(200))
+    coords[7, 0] = sc.SC_BATCH_MAX + 1
+    sc.sc_hash_build(torch.from_numpy(coords).to(DEV), table, counts)
+    assert sc.sc_counts_read(counts, check=False).status == sc.SC_ERANGE
+
+
 # ---- dense location table ---------------------------------------------------------------------
 @pytest.mark.parametrize("n,box", [(1, (1, 4, 4, 4)), (63, (3, 8, 8, 8)), (2000, (3, 64, 64, 64)), (50000, (3, 64, 64, 41))])
 def test_grid_finds_every_key(n, box):
@@ -308,9 +447,9 @@ def test_empty_input():
 def test_domain_edges_and_batches():
     """Voxels on the faces of the key domain: probes that leave it must miss, not wrap."""
     say("domain edges")
-    m = sc.SC_COORD_MAX if hasattr(sc, "SC_COORD_MAX") else 65534
+    m = sc.SC_COORD_MAX
     pts = []
-    for b in (0, 5, m):
+    for b in (0, 5, sc.SC_BATCH_MAX):
         for x in (0, 1, m - 1, m):
             for y in (0, m):
                 for z in (0, 1, m):
