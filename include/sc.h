@@ -5,6 +5,7 @@
  * (Section III-C: "create location table, create offset table, compute result"):
  *
  *     sc_hash_build   location table: coordinate -> input row        (Section III-C.1)
+ *     (sc_hash_rebuild: the same into a table that is already initialised, without refilling it)
  *     sc_kmap_build   offset table / rulebook of (in,out) pairs       (Section III-C.2, III-B, III-D)
  *     sc_conv_fwd     out[o] = sum_k sum_{(i,o) in M_k} in[i] . W[k]   (Algorithm 2, Section III-C.3)
  *
@@ -161,12 +162,14 @@ size_t sc_kmap_bytes(int64_t n, int K, int stride, int mode);
 size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode);
 
 /* Build the kernel map.
- *   d_table       table built by sc_hash_build over the same d_coords (required for SC_SUBM).
+ *   d_table       table built by sc_hash_build / sc_hash_rebuild over the same d_coords (required
+ *                 for SC_SUBM).
  *                 SC_STRIDED layers do not look anything up in it (Section III-D builds the
  *                 output side only): pass NULL and the build is self-contained - it then also
  *                 resets *d_counts the way sc_hash_build does (n_in = n, status 0); pass the
- *                 table of a preceding sc_hash_build and *d_counts is left as that call set it,
- *                 including SC_EDUP, which only sc_hash_build can detect
+ *                 table of a preceding sc_hash_build / sc_hash_rebuild and *d_counts is left as
+ *                 that call set it (plus what a rebuild left in the table header), including
+ *                 SC_EDUP, which only those two can detect
  *   mode          SC_SUBM (stride must be 1, K odd, K <= SC_K_MAX) or SC_STRIDED (2 <= K <=
  *                 SC_K_MAX, 1 <= stride <= K, no padding: input p pairs with output cell q at
  *                 offset d iff p = q*stride + d; K == stride <= 4 is the down-sampling layer of
@@ -280,8 +283,9 @@ int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, int mode,
                    int32_t* d_pairs_in, int32_t* d_pairs_out, int32_t* d_offset_start,
                    void* stream);
 
-/* Look up coordinates in a table built by sc_hash_build: d_rows[i] = row index of d_query[i],
- * or -1 if absent.  (Not on the layer's hot path; lets callers and tests read the table.) */
+/* Look up coordinates in a table built by sc_hash_build / sc_hash_rebuild: d_rows[i] = row index
+ * of d_query[i], or -1 if absent.  n_table is only range-checked (the table knows its capacity).
+ * (Not on the layer's hot path; lets callers and tests read the table.) */
 int sc_hash_lookup(const void* d_table, int64_t n_table,
                    const int32_t* d_query, int64_t n_query, int32_t* d_rows, void* stream);
 
