@@ -107,12 +107,15 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     extern __shared__ __align__(16) uint4 w_lds[];                   // [K3][CB][KS][64]
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
-    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NT + (wv >> 2);
     const int q = wv & 3;
     SC_MARK(0);
     int64_t n_out = n_out_cap;
     if (!FUSED && *n_out_ptr < n_out) n_out = *n_out_ptr;
-    if (xcd_unit(blockIdx.x, gridDim.x) * NT * TILE >= n_out) return;   // no rows here: the whole workgroup leaves
+    // the grid covers the caller's row capacity; the rows that exist are spread over all XCDs and
+    // a workgroup that gets none leaves at once (the whole workgroup, before any barrier)
+    const int64_t unit = xcd_unit_of(blockIdx.x, (n_out + NT * TILE - 1) / (NT * TILE));
+    if (unit < 0) return;
+    const int64_t tile = unit * NT + (wv >> 2);
     const int64_t row = tile * TILE + q * 16 + r;
     const bool group_ok = tile * TILE + q * 16 < n_out;             // uniform per wavefront
 
@@ -255,7 +258,6 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
-    const int64_t tile = xcd_unit(blockIdx.x, gridDim.x) * NWV + wv;
     uint4* w_lds = smem;
     constexpr int STAGE = RC ? 4 * 16 * RB : 0;      // bytes of the per-wavefront staging area (one part per group)
     char* stage = reinterpret_cast<char*>(smem + 2 * WK) + wv * STAGE;
@@ -263,9 +265,12 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     SC_MARK(0);
     int64_t n_out = n_out_cap;
     if (!FUSED && *n_out_ptr < n_out) n_out = *n_out_ptr;
-    // the grid covers the caller's row capacity; a workgroup whose tiles all lie past the rows
-    // that exist leaves at once (the same decision in every wavefront, before any barrier)
-    if (xcd_unit(blockIdx.x, gridDim.x) * NWV * TILE >= n_out) return;
+    // the grid covers the caller's row capacity; the rows that exist are spread over all XCDs and
+    // a workgroup that gets none leaves at once (the same decision in every wavefront, before
+    // any barrier)
+    const int64_t unit = xcd_unit_of(blockIdx.x, (n_out + NWV * TILE - 1) / (NWV * TILE));
+    if (unit < 0) return;
+    const int64_t tile = unit * NWV + wv;
     const bool tile_ok = tile * TILE < n_out;
 
     uint32_t mg[4] = {0u, 0u, 0u, 0u};

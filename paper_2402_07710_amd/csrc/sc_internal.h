@@ -242,6 +242,14 @@ __device__ inline int64_t xcd_unit(unsigned block, unsigned grid) {
     const unsigned chunk = grid / NUM_XCD;
     return (int64_t)(block % NUM_XCD) * chunk + block / NUM_XCD;
 }
+// The same when the grid was sized for a bound and only `units` units exist (output rows are
+// counted on the device): the units that exist are dealt out in eighths, so all XCDs work, and a
+// workgroup without a unit gets -1.  Needs gridDim.x >= xcd_grid(units).
+__device__ inline int64_t xcd_unit_of(unsigned block, int64_t units) {
+    const int64_t chunk = (units + NUM_XCD - 1) / NUM_XCD;
+    const int64_t u = (int64_t)(block % NUM_XCD) * chunk + block / NUM_XCD;
+    return (block / NUM_XCD < chunk && u < units) ? u : -1;
+}
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
