@@ -321,52 +321,60 @@ k_fill_rows(int4* __restrict__ nbr16, int K3, const sc_counts* __restrict__ coun
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < vec; i += nthr) nbr16[i] = make_int4(-1, -1, -1, -1);
 }
 
-template <typename F>
-__device__ inline void for_each_candidate(const int4 c, int K, int s, F&& f) {
-    int j = 0;
-    for (int dx = 0; dx < K; ++dx) {
-        const int tx = c.y - dx;
-        if (tx < 0 || tx % s) continue;
-        for (int dy = 0; dy < K; ++dy) {
-            const int ty = c.z - dy;
-            if (ty < 0 || ty % s) continue;
-            for (int dz = 0; dz < K; ++dz) {
-                const int tz = c.w - dz;
-                if (tz < 0 || tz % s) continue;
-                f(j++, (dx * K + dy) * K + dz, tx / s, ty / s, tz / s);
-            }
-        }
-    }
+// Candidate j of the input at c, or k < 0 if it has fewer.  Along one axis the offsets that can
+// pair coordinate p with a cell are d = p mod s, p mod s + s, ... below K and not above p (the
+// cell coordinate (p - d)/s must not be negative); candidates are numbered with x slowest and z
+// fastest, offsets ascending, i.e. in ascending order of the offset number k.
+struct Candidate {
+    int k;                 // offset number, -1: no such candidate
+    int qx, qy, qz;        // the output cell
+};
+__device__ inline int axis_options(int p, int K, int s) {
+    const int top = p < K - 1 ? p : K - 1;
+    return (top - p % s) / s + 1;                  // p mod s <= top always: s <= K and p mod s <= p
+}
+__device__ inline Candidate candidate(const int4 c, int K, int s, int j) {
+    const int cy = axis_options(c.z, K, s), cz = axis_options(c.w, K, s), cx = axis_options(c.y, K, s);
+    Candidate r;
+    r.k = -1; r.qx = r.qy = r.qz = 0;
+    if (j >= cx * cy * cz) return r;
+    const int dz = c.w % s + (j % cz) * s, dy = c.z % s + ((j / cz) % cy) * s, dx = c.y % s + (j / (cz * cy)) * s;
+    r.k = (dx * K + dy) * K + dz;
+    r.qx = (c.y - dx) / s; r.qy = (c.z - dy) / s; r.qz = (c.w - dz) / s;
+    return r;
 }
 
+// One thread per candidate (input i = id / maxc, candidate j = id % maxc): the inputs' candidates
+// are independent, and with a thread each their compare-and-swaps are all in flight together.
 __global__ void __launch_bounds__(256)
 k_gstrided_insert(const int4* __restrict__ coords, int64_t n, int K, int s, int maxc, uint4* oslots, uint32_t omask,
                   int32_t* __restrict__ cand_slot, sc_counts* counts) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id >= n * maxc) return;
+    const int64_t i = id / maxc;
+    const int j = (int)(id - i * maxc);
     const int4 c = coords[i];
-    int32_t* mine = cand_slot + i * maxc;
-    for (int j = 0; j < maxc; ++j) mine[j] = -1;
+    int32_t myslot = -1;
     if (!in_domain4(c.x, c.y, c.z, c.w)) {
-        latch_status(counts, SC_ERANGE);
-        return;
-    }
-    for_each_candidate(c, K, s, [&](int j, int, int qx, int qy, int qz) {
-        const uint64_t key = pack_key(c.x, qx, qy, qz);
-        int32_t myslot = -1;
-        for (uint32_t t = 0; t <= omask + REHASH_MAX; ++t) {
-            const uint32_t slot = probe_slot(key, t, omask);
-            const uint64_t cur = atomicCAS(reinterpret_cast<unsigned long long*>(&oslots[slot]),
-                                           (unsigned long long)KEY_EMPTY, (unsigned long long)key);
-            if (cur == KEY_EMPTY || cur == key) {
-                myslot = (int32_t)slot;
-                break;
+        if (j == 0) latch_status(counts, SC_ERANGE);
+    } else {
+        const Candidate q = candidate(c, K, s, j);
+        if (q.k >= 0) {
+            const uint64_t key = pack_key(c.x, q.qx, q.qy, q.qz);
+            for (uint32_t t = 0; t <= omask + REHASH_MAX; ++t) {
+                const uint32_t slot = probe_slot(key, t, omask);
+                const uint64_t cur = atomicCAS(reinterpret_cast<unsigned long long*>(&oslots[slot]),
+                                               (unsigned long long)KEY_EMPTY, (unsigned long long)key);
+                if (cur == KEY_EMPTY || cur == key) {
+                    myslot = (int32_t)slot;
+                    break;
+                }
             }
+            if (myslot >= 0) atomicMin(reinterpret_cast<int32_t*>(&oslots[myslot]) + 2, (int32_t)id);
+            else latch_status(counts, SC_EFULL);
         }
-        if (myslot >= 0) atomicMin(reinterpret_cast<int32_t*>(&oslots[myslot]) + 2, (int32_t)(i * maxc + j));
-        else latch_status(counts, SC_EFULL);
-        mine[j] = myslot;
-    });
+    }
+    cand_slot[id] = myslot;
 }
 
 __global__ void __launch_bounds__(256)
@@ -375,41 +383,49 @@ k_gstrided_pairs(const int4* __restrict__ coords, int64_t n, int K, int s, int m
                  const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
                  const int32_t* __restrict__ block_prefix, int32_t* __restrict__ nbr,
                  int4* __restrict__ out_coords, KmapHeader* hdr, KmapHeader hdr_value) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i == 0) *hdr = hdr_value;
-    if (i >= n) return;
+    const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (id == 0) *hdr = hdr_value;
+    if (id >= n * maxc) return;
+    const int32_t sl = cand_slot[id];
+    if (sl < 0) return;
+    const int64_t i = id / maxc;
     const int4 c = coords[i];
-    if (!in_domain4(c.x, c.y, c.z, c.w)) return;
-    const int K3 = K * K * K;
-    for_each_candidate(c, K, s, [&](int j, int k, int qx, int qy, int qz) {
-        const int32_t sl = cand_slot[i * maxc + j];
-        if (sl < 0) return;
-        const int32_t r = (int32_t)oslots[sl].z;               // the cell's first candidate
-        const int32_t o = block_prefix[r >> 10] + word_prefix[r >> 6] +
-                          __popcll(flagword[r >> 6] & ((1ull << (r & 63)) - 1ull));
-        // one input per (output row, offset): a plain store
-        nbr[((int64_t)(o >> 6) * K3 + k) * TILE + (o & 63)] = (int32_t)i;
-        if (r == (int32_t)(i * maxc + j)) out_coords[o] = make_int4(c.x, qx, qy, qz);
-    });
+    const Candidate q = candidate(c, K, s, (int)(id - i * maxc));
+    const int32_t r = (int32_t)oslots[sl].z;                   // the cell's first candidate
+    const int32_t o = block_prefix[r >> 10] + word_prefix[r >> 6] +
+                      __popcll(flagword[r >> 6] & ((1ull << (r & 63)) - 1ull));
+    // one input per (output row, offset): a plain store
+    nbr[((int64_t)(o >> 6) * (K * K * K) + q.k) * TILE + (o & 63)] = (int32_t)i;
+    if (r == (int32_t)id) out_coords[o] = make_int4(c.x, q.qx, q.qy, q.qz);
 }
 
-// Group masks of a finished offset table: one wavefront per tile votes on every offset line.
+// Group masks of a finished offset table: one workgroup per tile; its four wavefronts share the
+// offset lines, eight lines in flight each, vote on them and merge their bits in LDS.
 __global__ void __launch_bounds__(256)
 k_masks_from_table(const int32_t* __restrict__ nbr, int K3, int mw, int64_t tiles, uint32_t* __restrict__ gmask,
                    const sc_counts* __restrict__ counts, int inverse) {
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ uint32_t mask_s[4 * ((343 + 31) / 32)];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t tile = blockIdx.x;
     // tiles past the last output row (inverse maps: the last fine row) are never read
     if (tile >= tiles || tile * TILE >= (inverse ? counts->n_in : counts->n_out)) return;
+    if (threadIdx.x < 4 * mw) mask_s[threadIdx.x] = 0u;
+    __syncthreads();
     const int32_t* tile_nbr = nbr + tile * (int64_t)K3 * TILE;
-    for (int wi = 0; wi < mw; ++wi) {
-        uint32_t word = 0;                 // lanes 0..3: the mask word of group `lane`
-        for (int kk = 0; kk < 32 && wi * 32 + kk < K3; ++kk) {
-            const uint64_t vote = __ballot(tile_nbr[(wi * 32 + kk) * TILE + lane] >= 0);
-            if (lane < 4 && ((vote >> (16 * lane)) & 0xffffull) != 0) word |= 1u << kk;
+    for (int k0 = w * 8; k0 < K3; k0 += 32) {       // the eight lines k0..k0+7 lie in one mask word
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = k0 + u < K3 ? tile_nbr[(k0 + u) * TILE + lane] : -1;
+        uint32_t bits = 0;                          // lanes 0..3: group `lane`
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint64_t vote = __ballot(v[u] >= 0);
+            if (lane < 4 && ((vote >> (16 * lane)) & 0xffffull) != 0) bits |= 1u << ((k0 + u) & 31);
         }
-        if (lane < 4) gmask[(tile * 4 + lane) * mw + wi] = word;
+        if (lane < 4 && bits) atomicOr(&mask_s[lane * mw + (k0 >> 5)], bits);
     }
+    __syncthreads();
+    if (threadIdx.x < 4 * mw) gmask[tile * (4 * mw) + threadIdx.x] = mask_s[threadIdx.x];
 }
 
 // ---- reading a map back -----------------------------------------------------------------------
@@ -613,7 +629,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
                       d_counts, d_table == nullptr ? 1 : 0, n, table_hdr);
         }
         const int64_t gblk = (nc + 1023) / 1024;
-        const unsigned gg = (unsigned)((n + 255) / 256);
+        const unsigned gg = (unsigned)((nc + 255) / 256);
         SC_LAUNCH(KID_STRIDED_INSERT, k_gstrided_insert, dim3(gg), dim3(256), 0, s, (const int4*)d_coords, n, K, stride,
                   maxc, g.oslots, g.omask, g.slot_of, d_counts);
         SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)gblk), dim3(1024), 0, s, nc,
@@ -629,7 +645,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
                   maxc, (const int32_t*)g.slot_of, (const uint4*)g.oslots, (const uint64_t*)g.flagword,
                   (const int32_t*)g.word_prefix, (const int32_t*)g.block_prefix, nbr, (int4*)d_out_coords,
                   (KmapHeader*)d_kmap, h);
-        SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
+        SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)L.tiles), dim3(256), 0, s,
                   (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask, (const sc_counts*)d_counts, 0);
         return SC_OK;
     }
@@ -657,7 +673,7 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
               (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
               (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, nbr, (int4*)d_out_coords,
               (KmapHeader*)d_kmap, h);
-    SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
+    SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)L.tiles), dim3(256), 0, s,
               (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask, (const sc_counts*)d_counts, 0);
     return SC_OK;
 }
@@ -687,7 +703,7 @@ extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int strid
     unsigned gb = (unsigned)((items + 3) / 4);
     if (gb > 4096) gb = 4096;
     SC_LAUNCH(KID_MISC, k_transpose_scatter, dim3(gb), dim3(256), 0, s, nbr, L.K3, d_counts, inv_nbr);
-    SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)((L.tiles + 3) / 4)), dim3(256), 0, s,
+    SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)L.tiles), dim3(256), 0, s,
               (const int32_t*)inv_nbr, L.K3, L.mw, L.tiles, inv_mask, d_counts, 1);
     return SC_OK;
 }
