@@ -115,6 +115,58 @@ def stage_bench(args, torch, sc, synth) -> int:
     return 0
 
 
+def inverse_bench(args, torch, sc, synth) -> int:
+    """The up-sampling layer that undoes cfg3's down-sampling (Section III-E): coarse rows with 64
+    channels -> the cfg2 voxel set with 32 channels, K = stride = 2.  The strided map exists
+    already (the encoder built it); one step = transposing it (sc_kmap_transpose) + the
+    convolution over the transposed map."""
+    dev = "cuda:0"
+    cfg = synth.make_config("cfg3")
+    coords = cfg["coords"]
+    N = len(coords)
+    d_coords = torch.from_numpy(coords).to(dev)
+    down = sc.LayerBuffers(N, 2, 2, "strided", 32, 64, "f16", device=dev)
+    down.kmap_build(d_coords, standalone=True)
+    n_c = int(down.read_counts().n_out)
+    feat_c = torch.from_numpy(synth.features(n_c, 64, "f16", 11)).to(dev).half().contiguous()
+    w = torch.from_numpy(synth.weights(8, 64, 32, "f16", 11)).to(dev).half().contiguous()
+    kmap_inv = torch.empty(sc.sc_kmap_bytes(N, 2, 2, "inverse"), dtype=torch.uint8, device=dev)
+    out = torch.empty((N, 32), dtype=torch.float16, device=dev)
+    ws = torch.empty(max(sc.sc_conv_workspace_bytes(2, 64, 32, "f16"), 16), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        sc.sc_kmap_transpose(down.kmap, N, 2, 2, down.counts, kmap_inv, stream)
+        sc.sc_conv_fwd(feat_c, w, out, kmap_inv, down.counts, 2, 2, "inverse", ws, stream, n_map=N)
+
+    step()
+    P = int(sc.sc_counts_read(down.counts, kmap_inv, N, 2, 2, "inverse").n_pairs)
+    flops = 2.0 * P * 64 * 32
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    sc.sc_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    prof = sc.sc_profile_read()
+    sc.sc_profile_enable(False)
+    print(json.dumps({
+        "metric": "effective TFLOP/s over active MACs, inverse layer incl. transposing the strided map",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "cfg3-inverse: K=2 stride 2 up-sampling 64->32 onto the cfg2 voxel set",
+                   "N_coarse": n_c, "N_fine": N, "P": P},
+        "kernels": {k: {"launches_per_step": l / args.steps, "avg_us": round(1e3 * t / l, 3)} for k, (l, t) in prof.items()},
+    }))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +202,8 @@ def main() -> int:
 
     if args.workload == "cfg2-stage":
         return stage_bench(args, torch, sc, synth)
+    if args.workload == "cfg3-inverse":
+        return inverse_bench(args, torch, sc, synth)
     cfg = synth.make_config(args.workload)
     coords, K, stride, mode = cfg["coords"], cfg["K"], cfg["stride"], cfg["mode"]
     C_in, C_out, dtype = cfg["C_in"], cfg["C_out"], cfg["dtype"]

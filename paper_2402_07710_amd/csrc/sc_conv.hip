@@ -642,6 +642,7 @@ static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream
         if (K3 == 8 && C_in == 32 && C_out == 64) SC_ROWS16(8, 1, 4, 2);
         if (K3 == 8 && C_in == 32 && C_out == 32) SC_ROWS16(8, 1, 2, 2);
         if (K3 == 8 && C_in == 64 && C_out == 64) SC_ROWS16(8, 2, 4, 2);
+        if (K3 == 8 && C_in == 64 && C_out == 32) SC_ROWS16(8, 2, 2, 2);      // the up-sampling twin of 32 -> 64
     }
 #undef SC_ROWS16
     *handled = false;

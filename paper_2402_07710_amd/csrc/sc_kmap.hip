@@ -508,8 +508,9 @@ k_write_starts(StartArg a, int count, int32_t* __restrict__ dst) {
 // One wavefront per coarse tile and offset line: row i of the fine set learns its coarse parent.
 __global__ void __launch_bounds__(256)
 k_transpose_scatter(const int32_t* __restrict__ nbr, int K3, const sc_counts* __restrict__ counts,
-                    int32_t* __restrict__ inv_nbr) {
+                    int32_t* __restrict__ inv_nbr, KmapHeader* hdr, KmapHeader hdr_value) {
     const int lane = threadIdx.x & 63;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *hdr = hdr_value;
     const int64_t tiles = (counts->n_out + TILE - 1) / TILE;
     const int64_t items = tiles * K3;
     const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
@@ -689,8 +690,10 @@ extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int strid
     KmapHeader h{};
     h.magic = KMAP_MAGIC; h.K = K; h.stride = stride; h.mode = SC_INVERSE;
     h.n_in = n; h.n_out_bound = n; h.tiles = L.tiles; h.mw = L.mw;
-    SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap_inv, h);
-    if (n == 0) return SC_OK;
+    if (n == 0) {
+        SC_LAUNCH(KID_KMAP_HEADER, k_kmap_header, dim3(1), dim3(64), 0, s, (KmapHeader*)d_kmap_inv, h);
+        return SC_OK;
+    }
     const int32_t* nbr = (const int32_t*)((const char*)d_kmap + L.off_nbr);
     int32_t* inv_nbr = (int32_t*)((char*)d_kmap_inv + L.off_nbr);
     uint32_t* inv_mask = (uint32_t*)((char*)d_kmap_inv + L.off_mask);
@@ -702,7 +705,8 @@ extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int strid
     int64_t items = L.tiles * L.K3;
     unsigned gb = (unsigned)((items + 3) / 4);
     if (gb > 4096) gb = 4096;
-    SC_LAUNCH(KID_MISC, k_transpose_scatter, dim3(gb), dim3(256), 0, s, nbr, L.K3, d_counts, inv_nbr);
+    SC_LAUNCH(KID_MISC, k_transpose_scatter, dim3(gb), dim3(256), 0, s, nbr, L.K3, d_counts, inv_nbr,
+              (KmapHeader*)d_kmap_inv, h);
     SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)L.tiles), dim3(256), 0, s,
               (const int32_t*)inv_nbr, L.K3, L.mw, L.tiles, inv_mask, d_counts, 1);
     return SC_OK;
