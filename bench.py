@@ -155,8 +155,25 @@ def inverse_bench(args, torch, sc, synth) -> int:
         step()
     prof = sc.sc_profile_read()
     sc.sc_profile_enable(False)
+    # the same layer straight from the strided map (sc_conv_up_fwd): no transposed map at all
+    out2 = torch.empty_like(out)
+
+    def step_direct():
+        sc.sc_conv_up_fwd(feat_c, N, w, out2, down.kmap, down.counts, 2, stream)
+
+    for _ in range(args.warmup):
+        step_direct()
+    torch.cuda.synchronize()
+    if not torch.equal(out, out2):
+        raise RuntimeError("sc_conv_up_fwd and the transposed map give different layers")
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step_direct()
+    torch.cuda.synchronize()
+    ms_direct = (time.perf_counter() - t0) * 1e3 / args.steps
     print(json.dumps({
         "metric": "effective TFLOP/s over active MACs, inverse layer incl. transposing the strided map",
+        "direct_from_strided_map": {"ms_per_step": ms_direct, "value": flops / (ms_direct * 1e-3) / 1e12, "unit": "TFLOP/s"},
         "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",

@@ -264,6 +264,26 @@ int sc_conv_fwd_grid(const void* d_feat_in, const int32_t* d_coords, int64_t n,
                      int K, int C_in, int C_out, int dtype_in, int dtype_out,
                      void* d_workspace, size_t workspace_bytes, void* stream);
 
+/* The inverse layer of a K == stride layer straight from that layer's own map, without
+ * sc_kmap_transpose (Section III-E: the pairs of the down-sampling layer with input and output
+ * swapped).  Every fine row has exactly one parent there, so the kernel walks the coarse rows,
+ * multiplies each by the W[k] of the offsets it has children at and stores the products at the
+ * children's rows: d_feat_fine[i][:] = d_feat_coarse[o][:] . d_weight[k] for the pair (i, o) of
+ * offset k.  The result equals sc_kmap_transpose + sc_conv_fwd(SC_INVERSE).
+ *   n_map          the n the strided map was built with (= rows of d_feat_fine)
+ *   d_feat_coarse  [n_out][C_in] of dtype_in, n_out = d_counts->n_out of that build
+ *   d_weight       [K^3][C_in][C_out] of dtype_in
+ *   d_feat_fine    [n_map][C_out] of dtype_out, every row overwritten
+ *   d_kmap         blob from sc_kmap_build(SC_STRIDED, K, stride = K)
+ * K = 2 with (C_in, C_out) one of (32,32), (64,32), (64,64), (128,64), or K = 3 with (32,32);
+ * dtype_in SC_F16 / SC_BF16, dtype_out SC_F32 or dtype_in.  SC_EINVAL otherwise (use the
+ * transposed map). */
+int sc_conv_up_fwd(const void* d_feat_coarse, int64_t n_map,
+                   const void* d_weight, void* d_feat_fine,
+                   const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts,
+                   int K, int C_in, int C_out, int dtype_in, int dtype_out,
+                   void* stream);
+
 /* ---- reading results back ------------------------------------------------------------------ */
 
 /* Fill n_pairs and per_offset from the kernel map (d_kmap may be NULL to skip that), copy the

@@ -30,7 +30,7 @@ SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_rebuild", "sc_hash_lookup"
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
            "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid",
-           "sc_conv_fwd_grid"]
+           "sc_conv_fwd_grid", "sc_conv_up_fwd"]
 
 
 class ScCounts(ctypes.Structure):
@@ -70,6 +70,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_hash_bytes": (sz, [i64]),
         "sc_hash_build": (i32, [vp, i64, vp, sz, vp, vp]),
         "sc_hash_rebuild": (i32, [vp, i64, vp, sz, i32, vp, vp]),
+        "sc_conv_up_fwd": (i32, [vp, i64, vp, vp, vp, sz, vp, i32, i32, i32, i32, i32, vp]),
         "sc_hash_lookup": (i32, [vp, i64, vp, i64, vp, vp]),
         "sc_out_bound": (i64, [i64, i32, i32, i32]),
         "sc_kmap_bytes": (sz, [i64, i32, i32, i32]),
@@ -194,6 +195,18 @@ def sc_kmap_build_grid(coords, grid, dims, epoch, K, kmap, counts, stream=None):
     _check(load().sc_kmap_build_grid(_ptr(coords), coords.shape[0], _ptr(grid), grid.numel() * grid.element_size(),
                                      *dims, epoch, K, _ptr(kmap), kmap.numel() * kmap.element_size(), _ptr(counts),
                                      _stream(stream)), "sc_kmap_build_grid")
+
+
+def sc_conv_up_fwd(feat_coarse, n_map, weight, feat_fine, kmap, counts, K, stream=None):
+    """Inverse layer of a K == stride layer from that layer's own map: feat_coarse [n_out, C_in],
+    weight [K^3, C_in, C_out], feat_fine [n_map, C_out]."""
+    C_in, C_out = weight.shape[1], weight.shape[2]
+    if tuple(weight.shape) != (K ** 3, C_in, C_out) or weight.dtype != feat_coarse.dtype or \
+            feat_coarse.shape[1] != C_in or tuple(feat_fine.shape) != (n_map, C_out):
+        raise ScError(SC_EINVAL, "sc_conv_up_fwd")
+    _check(load().sc_conv_up_fwd(_ptr(feat_coarse), n_map, _ptr(weight), _ptr(feat_fine), _ptr(kmap),
+                                 kmap.numel() * kmap.element_size(), _ptr(counts), K, C_in, C_out,
+                                 DTYPES[feat_coarse.dtype], DTYPES[feat_fine.dtype], _stream(stream)), "sc_conv_up_fwd")
 
 
 def sc_conv_fwd_grid(feat_in, coords, grid, dims, epoch, weight, feat_out, K, workspace, stream=None):

@@ -95,12 +95,18 @@ __device__ inline void store_acc(void* __restrict__ out, int out_f32, int64_t ro
 // FUSED: there is no kernel map; the K^3 neighbours of a row are looked up in the dense location
 // table right here (one index computation and one 8-byte load each, all in flight together), and
 // the group's mask is a vote over what was found.  n_out_cap is then the number of rows.
-template <int DT, int K3, int KS, int CB, int NT, int FUSED>
+// UP: the inverse (up-sampling) layer of a K == stride layer, straight from that layer's own map
+// (Section III-E: the same pairs with input and output swapped).  The wavefront's 16 rows are
+// coarse rows, read in place; entry k of a row's table column names the fine row that receives
+// row . W[k].  Every fine row has exactly one parent, so results are stored, not accumulated, and
+// nothing needs to be transposed first.
+template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0>
 __global__ void __launch_bounds__(256 * NT)
 k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw, void* __restrict__ out, int out_f32,
               const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
     static_assert(K3 <= 32, "one mask word per group");
     static_assert(!FUSED || K3 == 27, "fused look-ups: 3x3x3 layers");
+    static_assert(!(FUSED && UP), "one or the other");
     const uint32_t* __restrict__ gmask = ms.gmask;
     const int32_t* __restrict__ nbr = ms.nbr;
     constexpr int C_in = KS * 32, C_out = CB * 16;
@@ -169,6 +175,32 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     SC_MARK(1);
     m = __builtin_amdgcn_readfirstlane(m);
 
+    if constexpr (UP) {
+        uint4 own[KS];                       // the coarse row itself: no gather
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            own[ks] = (group_ok && row < n_out) ? reinterpret_cast<const uint4*>(feat + row * C_in)[qq + ks * 4]
+                                                : make_uint4(0, 0, 0, 0);
+        __syncthreads();
+        SC_MARK(2);
+#pragma unroll
+        for (int k = 0; k < K3; ++k) {
+            if (m & (1u << k)) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    f32x4 d = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        d = mfma16x16x32<DT>(w_lds[((k * CB + cb) * KS + ks) * 64 + lane], own[ks], d);
+                    if (e[k] >= 0) store_acc<DT>(out, out_f32, e[k], C_out, cb * 16 + qq * 4, d);
+                }
+            }
+        }
+        SC_MARK(3);
+        SC_MARK(4);
+        SC_MARK(5);
+        return;
+    }
     // every gather of the group in flight at once
     uint4 fb[K3][KS];
 #pragma unroll
@@ -610,10 +642,10 @@ k_conv_f32_small(const float* __restrict__ feat, const float* __restrict__ w, fl
     }
 }
 
-template <int DT, int K3, int KS, int CB, int NT, int FUSED>
+template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0>
 static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_rows16<DT, K3, KS, CB, NT, FUSED>;
+    auto fn = k_conv_rows16<DT, K3, KS, CB, NT, FUSED, UP>;
     const size_t lds = (size_t)K3 * CB * KS * 64 * sizeof(uint4);
     static bool attr_set = false;           // once per instantiation; the value never changes
     if (!attr_set) {
@@ -663,6 +695,24 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
     }
     SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + NWV - 1) / NWV)), dim3(64 * NWV), lds, s, feat, wp, out, out_f32,
               ms, counts, n_out_cap);
+    return SC_OK;
+}
+
+// Up-sampling straight from the strided layer's map: shapes with a dedicated kernel.
+template <int DT>
+static int launch_up(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp,
+                     void* out, int out_f32, const MapSource& ms, const int64_t* counts, int64_t n_out_cap,
+                     bool* handled) {
+    *handled = true;
+#define SC_UP16(K3V, KSV, CBV) \
+    return launch_rows16<DT, K3V, KSV, CBV, 2, 0, 1>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
+    if (K3 == 8 && C_in == 64 && C_out == 32) SC_UP16(8, 2, 2);
+    if (K3 == 8 && C_in == 32 && C_out == 32) SC_UP16(8, 1, 2);
+    if (K3 == 8 && C_in == 64 && C_out == 64) SC_UP16(8, 2, 4);
+    if (K3 == 8 && C_in == 128 && C_out == 64) SC_UP16(8, 4, 4);
+    if (K3 == 27 && C_in == 32 && C_out == 32) SC_UP16(27, 1, 2);
+#undef SC_UP16
+    *handled = false;
     return SC_OK;
 }
 
@@ -795,6 +845,36 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
                   (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
                   C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
     return SC_OK;
+}
+
+extern "C" int sc_conv_up_fwd(const void* d_feat_coarse, int64_t n_map, const void* d_weight, void* d_feat_fine,
+                              const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts, int K, int C_in,
+                              int C_out, int dtype_in, int dtype_out, void* stream) {
+    if (n_map < 0 || n_map > SC_N_MAX || K < 2 || K > 4 || C_in < 1 || C_out < 1) return SC_EINVAL;
+    if (d_weight == nullptr || d_kmap == nullptr || d_counts == nullptr) return SC_EINVAL;
+    if (n_map > 0 && (d_feat_coarse == nullptr || d_feat_fine == nullptr)) return SC_EINVAL;
+    if (!aligned16(d_feat_coarse) || !aligned16(d_weight) || !aligned16(d_feat_fine) || !aligned16(d_kmap) ||
+        !aligned16(d_counts))
+        return SC_EINVAL;
+    if (dtype_in != SC_F16 && dtype_in != SC_BF16) return SC_EINVAL;
+    if (dtype_out != SC_F32 && dtype_out != dtype_in) return SC_EINVAL;
+    if (kmap_bytes < sc_kmap_bytes(n_map, K, K, SC_STRIDED)) return SC_ECAP;
+    const KmapLayout L = kmap_layout(sc_out_bound(n_map, K, K, SC_STRIDED), K);
+    if (L.tiles == 0) return SC_OK;
+    MapSource ms{};
+    ms.gmask = (const uint32_t*)((const char*)d_kmap + L.off_mask);
+    ms.nbr = (const int32_t*)((const char*)d_kmap + L.off_nbr);
+    bool handled = false;
+    // the kernel walks the coarse rows: counts->n_out of them, at most the map's bound
+    const int rc = dtype_in == SC_F16
+                       ? launch_up<SC_F16>(L.K3, C_in, C_out, L.tiles, (hipStream_t)stream, (const uint16_t*)d_feat_coarse,
+                                           (const uint4*)d_weight, d_feat_fine, dtype_out == SC_F32 ? 1 : 0, ms,
+                                           &d_counts->n_out, n_map, &handled)
+                       : launch_up<SC_BF16>(L.K3, C_in, C_out, L.tiles, (hipStream_t)stream, (const uint16_t*)d_feat_coarse,
+                                            (const uint4*)d_weight, d_feat_fine, dtype_out == SC_F32 ? 1 : 0, ms,
+                                            &d_counts->n_out, n_map, &handled);
+    if (rc != SC_OK) return rc;
+    return handled ? SC_OK : SC_EINVAL;
 }
 
 extern "C" int sc_conv_fwd_grid(const void* d_feat_in, const int32_t* d_coords, int64_t n, const void* d_grid,

@@ -103,5 +103,14 @@ def test_host_side_argument_errors(lib):
                                 96, 1 << 20, None) == binding.SC_EINVAL                 # 16-bit layers only
     assert lib.sc_conv_fwd_grid(16, 32, 10, 48, gb, 1, 8, 8, 8, 1, 64, 80, 3, 32, 32, binding.SC_F16, binding.SC_F16,
                                 96, 16, None) == binding.SC_ECAP                        # workspace too small
+    # sc_conv_up_fwd(feat_coarse, n_map, weight, feat_fine, kmap, kmap_bytes, counts, K, C_in, C_out, dt_in, dt_out, stream)
+    F16, F32 = binding.SC_F16, binding.SC_F32
+    assert lib.sc_conv_up_fwd(16, 10, 32, 48, 64, 1 << 20, 80, 5, 32, 32, F16, F16, None) == binding.SC_EINVAL   # K
+    assert lib.sc_conv_up_fwd(16, 10, 32, 48, 64, 1 << 20, 80, 2, 32, 32, F32, F32, None) == binding.SC_EINVAL   # dtype
+    assert lib.sc_conv_up_fwd(16, 10, 32, 48, 64, 1 << 20, 80, 2, 32, 32, F16, binding.SC_BF16, None) == binding.SC_EINVAL
+    assert lib.sc_conv_up_fwd(16, 10, 32, 48, 64, 8, 80, 2, 32, 32, F16, F16, None) == binding.SC_ECAP           # map blob
+    assert lib.sc_conv_up_fwd(16, 10, 32, 48, 64, 1 << 20, 80, 2, 32, 48, F16, F16, None) == binding.SC_EINVAL   # shape
+    assert lib.sc_conv_up_fwd(16, 10, None, 48, 64, 1 << 20, 80, 2, 32, 32, F16, F16, None) == binding.SC_EINVAL
+    assert lib.sc_conv_up_fwd(17, 10, 32, 48, 64, 1 << 20, 80, 2, 32, 32, F16, F16, None) == binding.SC_EINVAL   # misaligned
     assert binding.strerror(binding.SC_EDUP) == "duplicate input coordinate"
     assert binding.strerror(12345) == "unknown status"

@@ -581,6 +581,61 @@ def test_inverse_layer(K, dtype, C_c, C_f):
     assert err <= TOL[dtype], err
 
 
+@pytest.mark.parametrize("K,dtype,C_c,C_f,out_dtype", [(2, "f16", 64, 32, None), (2, "bf16", 32, 32, None),
+                                                       (2, "f16", 64, 64, "f32"), (2, "bf16", 128, 64, None),
+                                                       (3, "f16", 32, 32, None)])
+def test_upsampling_from_the_strided_map(K, dtype, C_c, C_f, out_dtype):
+    """sc_conv_up_fwd: the inverse layer without a transposed map, against the oracle's inverse
+    layer and against the library's own transpose + sc_conv_fwd(SC_INVERSE)."""
+    say(f"up-sampling K={K} {dtype} {C_c}->{C_f} out={out_dtype}")
+    coords = synth.lidar_scene(5)[:20011]
+    n = len(coords)
+    d_coords = torch.from_numpy(coords).to(DEV)
+    buf = sc.LayerBuffers(n, K, K, "strided", 32, 32, "f16", device=DEV)
+    buf.kmap_build(d_coords, standalone=True)
+    n_c = int(buf.read_counts().n_out)
+    ref_km = oracle.kmap(coords, K, K, "strided")
+    assert n_c == ref_km["n_out"]
+    feat_c = synth.features(n_c, C_c, dtype, 9)
+    w = synth.weights(K ** 3, C_c, C_f, dtype, 9)
+    odt = TDT[out_dtype or dtype]
+    fine = torch.full((n, C_f), float("nan"), dtype=odt, device=DEV)
+    sc.sc_conv_up_fwd(to_dev(feat_c, dtype), n, to_dev(w, dtype), fine, buf.kmap, buf.counts, K)
+    ref = oracle.conv(feat_c, w, oracle.transpose_map(ref_km), threads=8)
+    got = fine.double().cpu().numpy()
+    assert np.isfinite(got).all(), "a fine row was not written"
+    assert rel_err(got, ref) <= TOL[dtype]
+    # the same layer through the transposed map: identical bits (one product per row either way)
+    kmap_inv = torch.empty(sc.sc_kmap_bytes(n, K, K, "inverse"), dtype=torch.uint8, device=DEV)
+    sc.sc_kmap_transpose(buf.kmap, n, K, K, buf.counts, kmap_inv)
+    fine2 = torch.empty((n, C_f), dtype=odt, device=DEV)
+    ws = torch.empty(max(sc.sc_conv_workspace_bytes(K, C_c, C_f, dtype), 16), dtype=torch.uint8, device=DEV)
+    sc.sc_conv_fwd(to_dev(feat_c, dtype), to_dev(w, dtype), fine2, kmap_inv, buf.counts, K, K, "inverse", ws, n_map=n)
+    assert torch.equal(fine, fine2)
+
+
+def test_upsampling_small_and_ragged():
+    say("up-sampling small")
+    for n in (1, 17, 64, 65, 700):
+        coords = synth.uniform_cells(n, 12, seed=n)
+        d_coords = torch.from_numpy(coords).to(DEV)
+        buf = sc.LayerBuffers(n, 2, 2, "strided", 32, 32, "f16", device=DEV)
+        buf.kmap_build(d_coords, standalone=True)
+        n_c = int(buf.read_counts().n_out)
+        ref_km = oracle.kmap(coords, 2, 2, "strided")
+        feat_c = synth.features(n_c, 64, "f16", n)
+        w = synth.weights(8, 64, 32, "f16", n)
+        fine = torch.full((n, 32), float("nan"), dtype=torch.float16, device=DEV)
+        sc.sc_conv_up_fwd(to_dev(feat_c, "f16"), n, to_dev(w, "f16"), fine, buf.kmap, buf.counts, 2)
+        ref = oracle.conv(feat_c, w, oracle.transpose_map(ref_km), threads=2)
+        got = fine.double().cpu().numpy()
+        assert np.isfinite(got).all()
+        assert rel_err(got, ref) <= TOL["f16"]
+    with pytest.raises(sc.ScError):
+        sc.sc_conv_up_fwd(to_dev(feat_c, "f16")[:, :32].contiguous(), n, to_dev(synth.weights(8, 32, 48, "f16", 1), "f16"),
+                          torch.empty((n, 48), dtype=torch.float16, device=DEV), buf.kmap, buf.counts, 2)
+
+
 # ---- the five named configurations at full size ----------------------------------------------
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "target64"])
 def test_named_config_full(name):
