@@ -636,6 +636,40 @@ def test_upsampling_small_and_ragged():
                           torch.empty((n, 48), dtype=torch.float16, device=DEV), buf.kmap, buf.counts, 2)
 
 
+def test_random_layers():
+    """A seeded sweep over layer kinds, kernel sizes, strides, channel counts, element types, sizes
+    and both location tables, each layer checked like the named ones (map bit-exact, output within
+    tolerance)."""
+    rng = np.random.default_rng(2024)
+    for it in range(48):
+        kind = rng.choice(["subm", "strided", "strided_general"])
+        dtype = str(rng.choice(["f16", "bf16", "f32"]))
+        if dtype == "f32":
+            C_in, C_out = int(rng.choice([3, 8, 16, 32, 48])), int(rng.choice([5, 16, 32, 64]))
+        else:
+            C_in, C_out = int(rng.choice([32, 64, 128])), int(rng.choice([16, 32, 48, 64, 128]))
+        if kind == "subm":
+            mode, K, s = "subm", int(rng.choice([1, 3, 3, 3, 5])), 1
+        elif kind == "strided":
+            mode, K = "strided", int(rng.choice([2, 2, 3, 4]))
+            s = K
+        else:
+            mode, K = "strided", int(rng.choice([3, 3, 4, 5]))
+            s = int(rng.integers(1, K))
+        g = int(rng.choice([6, 12, 20, 30]))
+        n = max(1, int(min(rng.integers(1, 12000), g ** 3 * 0.6)))
+        coords = synth.uniform_cells(n, g, seed=int(rng.integers(1 << 30)))
+        coords[:, 0] = rng.integers(0, 3, size=n)
+        coords = np.unique(coords, axis=0)
+        rng.shuffle(coords)
+        coords = np.ascontiguousarray(coords.astype(np.int32))
+        if mode == "strided" and K != s:
+            coords = coords[:3000]
+        grid = (3, g, g, g) if mode == "subm" and rng.random() < 0.3 else None
+        say(f"random layer {it}: {mode} K={K} s={s} {dtype} {C_in}->{C_out} n={len(coords)} box={g} grid={grid is not None}")
+        check_layer(coords, K, s, mode, C_in, C_out, dtype, seed=it, threads=8, grid_dims=grid)
+
+
 # ---- the five named configurations at full size ----------------------------------------------
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "target64"])
 def test_named_config_full(name):
