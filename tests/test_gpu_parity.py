@@ -263,6 +263,39 @@ def test_hash_rebuild_errors_surface_at_the_map_build():
     assert sc.sc_counts_read(counts, check=False).status == sc.SC_ECAP
 
 
+def test_hash_rebuild_of_a_large_table():
+    """Above 16 MiB of table a rebuild fills the table after all (and then reports its errors
+    like sc_hash_build): same results as for small tables, whichever way the library takes."""
+    say("hash rebuild, large table")
+    n = 140_000                                             # capacity 2^21 slots = 32 MiB
+    table, counts = fresh_table(n)
+    kmap = torch.empty(sc.sc_kmap_bytes(n, 3, 1, "subm"), dtype=torch.uint8, device=DEV)
+    prev = None
+    for epoch in range(3):
+        coords = synth.uniform_cells(n, 64, seed=100 + epoch)
+        d = torch.from_numpy(coords).to(DEV)
+        if epoch == 0:
+            sc.sc_hash_build(d, table, counts)
+        else:
+            sc.sc_hash_rebuild(d, table, epoch, counts)
+        assert sc.sc_counts_read(counts).status == 0
+        assert np.array_equal(lookup_np(table, n, coords[::7]), np.arange(n)[::7])
+        if prev is not None:                                # the previous build's keys are gone
+            gone = prev[~(prev[:, None, :] == coords[None, :64, :]).all(-1).any(-1)][:5000]
+            want = {tuple(c): i for i, c in enumerate(coords.tolist())}
+            assert np.array_equal(lookup_np(table, n, gone), np.array([want.get(tuple(c), -1) for c in gone.tolist()]))
+        sc.sc_kmap_build(d, table, 3, 1, "subm", None, kmap, None, counts)
+        h = sc.sc_counts_read(counts, kmap, n, 3, 1, "subm")
+        ref = oracle.kmap(coords, 3, 1, "subm")
+        assert h.status == 0 and h.n_pairs == ref["offset_start"][-1]
+        assert list(h.per_offset[:27]) == list(np.diff(ref["offset_start"]))
+        prev = coords
+    dup = prev.copy()
+    dup[1234] = dup[99999]
+    sc.sc_hash_rebuild(torch.from_numpy(dup).to(DEV), table, 3, counts)
+    assert sc.sc_counts_read(counts, check=False).status == sc.SC_EDUP
+
+
 def test_hash_batch_index_range():
     say("hash batch range")
     coords = synth.uniform_cells(200, 8, seed=3)
