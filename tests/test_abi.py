@@ -37,7 +37,7 @@ def test_counts_struct_layout():
 
 
 def test_size_queries(lib):
-    # 16-byte slots, capacity = power of two >= 4n (at least 1024)
+    # 16-byte slots, capacity = power of two >= 8n (at least 1024), plus the 256-byte header
     assert lib.sc_hash_bytes(0) == 1024 * 16 + 256
     assert lib.sc_hash_bytes(128) == 1024 * 16 + 256
     assert lib.sc_hash_bytes(129) == 2048 * 16 + 256
