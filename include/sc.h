@@ -83,8 +83,11 @@ typedef struct sc_counts {
 /* ---- location table (Section III-C.1; the paper offers a dense array or a hash table, this
  * library uses an open-addressing hash table keyed on the packed 64-bit (b,x,y,z)) ---------- */
 
-/* Bytes of the table for n keys: 16 bytes per slot, capacity = power of two >= 8n and >= 1024
- * slots, so the load factor stays <= 1/8, plus a 256-byte header. */
+/* Bytes of the table for n keys: 16 bytes per slot plus a 256-byte header.  The capacity is a
+ * power of two, at least 1024 slots and at least 8n (load factor <= 1/8); small tables are made
+ * sparser still - up to 32 slots per key while the table stays within 2^22 slots (64 MiB) -
+ * because shorter probe chains save round trips and a table of that size can be built again
+ * without being refilled (sc_hash_rebuild). */
 size_t sc_hash_bytes(int64_t n);
 
 /* Build the table coordinate -> row index over d_coords [n][4] (b,x,y,z).  Also resets
@@ -105,7 +108,7 @@ int sc_hash_build(const int32_t* d_coords, int64_t n,
  * SC_ECAP of such a build are kept in the table's header and latched into d_counts->status by
  * the next sc_kmap_build that is given this table; sc_hash_lookup alone does not report them
  * (a duplicated coordinate maps to one of its rows, a coordinate outside the domain is
- * absent).  Tables above 16 MiB are filled all the same, with the capacity for n (measured
+ * absent).  Tables above 64 MiB are filled all the same, with the capacity for n (measured
  * faster there: the fill leaves the table in the last-level cache for the probes that
  * follow), and then report like sc_hash_build.
  * SC_EINVAL if epoch is outside 1..SC_HASH_EPOCH_MAX. */

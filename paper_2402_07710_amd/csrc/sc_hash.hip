@@ -125,7 +125,7 @@ using namespace sc;
 
 extern "C" size_t sc_hash_bytes(int64_t n) {
     if (n < 0 || n > SC_N_MAX) return 0;
-    return (size_t)hash_capacity(n) * sizeof(uint4) + sizeof(TableHeader);
+    return (size_t)table_capacity(n) * sizeof(uint4) + sizeof(TableHeader);
 }
 
 static int hash_build(const int32_t* d_coords, int64_t n, void* d_table, size_t table_bytes, int epoch,
@@ -136,11 +136,10 @@ static int hash_build(const int32_t* d_coords, int64_t n, void* d_table, size_t 
     if (table_bytes < sc_hash_bytes(n)) return SC_ECAP;
     hipStream_t s = (hipStream_t)stream;
     HashTable t = table_view(d_table, n);
-    // A build with an epoch >= 1 may skip the fill.  It does so for tables up to 16 MiB; above
+    // A build with an epoch >= 1 may skip the fill.  It does so for tables up to 64 MiB; above
     // that the fill pays for itself: written front to back it leaves the table in the last-level
     // cache, where the scattered inserts and the 26 probes per row of the map build then find it
-    // (measured at 2M rows, 256 MiB of table: insert + map build 199 us without the fill, 183 us with).
-    constexpr uint64_t NO_FILL_SLOTS_MAX = 1ull << 20;
+    // (measured at 10^6 rows, 256 MiB of table: insert + map build 199 us without the fill, 183 us with).
     if (epoch == 0 || (uint64_t)t.mask + 1 > NO_FILL_SLOTS_MAX) {
         if (int rc = launch_table_fill(t.slots, (uint64_t)t.mask + 1, 0, d_counts, n, s, t.hdr, (uint32_t)epoch)) return rc;
         if (n > 0)

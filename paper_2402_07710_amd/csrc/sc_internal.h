@@ -57,14 +57,25 @@ __host__ __device__ inline uint32_t probe_slot(uint64_t key, uint32_t t, uint32_
     return slot & mask;
 }
 
-// capacity: power of two >= 8n, at least 1024 slots.  Probe chains decide the cost of the build and
-// of the kernel map (every extra attempt is one more dependent round trip for the whole
-// wavefront), and memory is cheap: measured on ~53k voxels, whole layer with capacity >= 2n
-// 121 us, >= 4n 46 us, >= 8n 37 us, >= 16n 36.5 us (the fill then grows faster than the probes shrink).
-inline uint64_t hash_capacity(int64_t n, uint64_t per_key = 8) {
+// Slots for n keys at `per_key` slots each: the next power of two, at least 1024.
+inline uint64_t hash_capacity(int64_t n, uint64_t per_key) {
     uint64_t cap = 1024;
     while (cap < per_key * (uint64_t)(n < 0 ? 0 : n)) cap <<= 1;
     return cap;
+}
+// Capacity of the location table.  Probe chains decide the cost of the build and of the kernel
+// map (every extra attempt is one more dependent round trip for the whole wavefront), and memory
+// is cheap.  What a sparser table costs is its fill - and a table that is built again skips the
+// fill as long as it has at most NO_FILL_SLOTS_MAX slots (sc_hash_rebuild).  So: 32 slots per key
+// while that stays within the no-fill size, never fewer than 8.  Measured, whole layers with the
+// table reused: ~53k voxels 8n 33.5 us, 16n 31.0, 32n 29.8; ~110k voxels 8n 78.4, 16n 73.0, 32n
+// 70.3; 10^6 voxels (filled every time) 8n 900, 16n 929, 32n 990.  (When every build still
+// filled the table, ~53k voxels: 2n 121 us, 4n 46, 8n 37, 16n 36.5.)
+constexpr uint64_t NO_FILL_SLOTS_MAX = 1ull << 22;      // 64 MiB of slots
+inline uint64_t table_capacity(int64_t n) {
+    const uint64_t dense = hash_capacity(n, 8), sparse = hash_capacity(n, 32);
+    const uint64_t capped = sparse < NO_FILL_SLOTS_MAX ? sparse : NO_FILL_SLOTS_MAX;
+    return dense > capped ? dense : capped;
 }
 
 // One 16-byte slot per key: {epoch | key (8 bytes), value (4), unused (4)}, so a probe is one
@@ -88,7 +99,7 @@ inline HashTable table_view(void* p, int64_t n) {
     HashTable t;
     t.hdr = (TableHeader*)p;
     t.slots = (uint4*)((char*)p + sizeof(TableHeader));
-    t.mask = (uint32_t)(hash_capacity(n) - 1);
+    t.mask = (uint32_t)(table_capacity(n) - 1);
     return t;
 }
 __host__ __device__ inline uint64_t slot_key(const uint4& s) { return (uint64_t)s.x | ((uint64_t)s.y << 32); }

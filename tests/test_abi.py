@@ -37,12 +37,17 @@ def test_counts_struct_layout():
 
 
 def test_size_queries(lib):
-    # 16-byte slots, capacity = power of two >= 8n (at least 1024), plus the 256-byte header
+    # 16-byte slots; capacity = power of two >= 32n while that is at most 2^22 slots, never below 8n
+    # or 1024; plus the 256-byte header
     assert lib.sc_hash_bytes(0) == 1024 * 16 + 256
-    assert lib.sc_hash_bytes(128) == 1024 * 16 + 256
-    assert lib.sc_hash_bytes(129) == 2048 * 16 + 256
-    assert lib.sc_hash_bytes(1000) == 8192 * 16 + 256
-    assert lib.sc_hash_bytes(1025) == 16384 * 16 + 256
+    assert lib.sc_hash_bytes(32) == 1024 * 16 + 256
+    assert lib.sc_hash_bytes(33) == 2048 * 16 + 256
+    assert lib.sc_hash_bytes(1000) == 32768 * 16 + 256
+    assert lib.sc_hash_bytes(1025) == 65536 * 16 + 256
+    assert lib.sc_hash_bytes(131072) == (1 << 22) * 16 + 256
+    assert lib.sc_hash_bytes(200000) == (1 << 22) * 16 + 256          # 16n < 2^22 <= 32n: capped
+    assert lib.sc_hash_bytes(524288) == (1 << 22) * 16 + 256          # exactly 8n
+    assert lib.sc_hash_bytes(524289) == (1 << 23) * 16 + 256          # 8n rules from here on
     assert lib.sc_hash_bytes(-1) == 0
     assert lib.sc_out_bound(500, 3, 1, binding.SC_SUBM) == 500
     assert lib.sc_out_bound(500, 2, 2, binding.SC_STRIDED) == 500
