@@ -44,7 +44,10 @@ template <int FRESH>
 __global__ void __launch_bounds__(256)
 k_hash_insert(const int4* __restrict__ coords, int64_t n, uint4* slots, uint32_t mask_fresh, uint32_t epoch,
               TableHeader* th, sc_counts* counts) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    // without a fill, workgroups are dealt to the XCDs the way the map build deals its tiles: the
+    // slots a row claims are then in the L2 that will probe for them (~53k voxels: 9.7 -> 8.4 us;
+    // after a fill the table is spread over the caches already and the plain order is faster)
+    const int64_t i = (FRESH ? (int64_t)blockIdx.x : xcd_unit(blockIdx.x, gridDim.x)) * blockDim.x + threadIdx.x;
     const uint32_t mask = FRESH ? mask_fresh : th->mask;      // a table keeps the capacity it was filled with
     if (!FRESH && blockIdx.x == 0) {
         int32_t* w = reinterpret_cast<int32_t*>(counts);
@@ -147,7 +150,7 @@ static int hash_build(const int32_t* d_coords, int64_t n, void* d_table, size_t 
                       (const int4*)d_coords, n, t.slots, t.mask, (uint32_t)epoch, t.hdr, d_counts);
     } else {
         // at least one workgroup: it also resets the counts and stamps the header
-        SC_LAUNCH(KID_HASH_INSERT, k_hash_insert<0>, dim3((unsigned)((n + 255) / 256 > 0 ? (n + 255) / 256 : 1)), dim3(256), 0,
+        SC_LAUNCH(KID_HASH_INSERT, k_hash_insert<0>, dim3(xcd_grid((n + 255) / 256 > 0 ? (n + 255) / 256 : 1)), dim3(256), 0,
                   s, (const int4*)d_coords, n, t.slots, t.mask, (uint32_t)epoch, t.hdr, d_counts);
     }
     return SC_OK;
