@@ -642,17 +642,26 @@ k_conv_f32_small(const float* __restrict__ feat, const float* __restrict__ w, fl
     }
 }
 
+// Large dynamic LDS has to be allowed per kernel, once on every device the kernel runs on: a flag
+// per device (a repeated call would be harmless, so a race between host threads is too).
+constexpr int MAX_DEVICES = 64;
+static int allow_lds(const void* fn, size_t lds, bool (&done)[MAX_DEVICES]) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return SC_EHIP;
+    if (!done[dev]) {
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return SC_EHIP;
+        done[dev] = true;
+    }
+    return SC_OK;
+}
+
 template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0>
 static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
     auto fn = k_conv_rows16<DT, K3, KS, CB, NT, FUSED, UP>;
     const size_t lds = (size_t)K3 * CB * KS * 64 * sizeof(uint4);
-    static bool attr_set = false;           // once per instantiation; the value never changes
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return SC_EHIP;
-        attr_set = true;
-    }
+    static bool allowed[MAX_DEVICES] = {};  // per instantiation
+    if (int rc = allow_lds((const void*)fn, lds, allowed)) return rc;
     const dim3 grid(xcd_grid((tiles + NT - 1) / NT));
     SC_LAUNCH(KID_CONV_MFMA, fn, grid, dim3(256 * NT), lds, s, feat, wp, out, out_f32, ms, counts, n_out_cap);
     return SC_OK;
@@ -687,12 +696,8 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
     auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, RC, FUSED>;
     const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (RC ? (size_t)NWV * 4 * 16 * KS * 64 : 0) +
                        (size_t)NWV * K3 * TILE * sizeof(int32_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return SC_EHIP;
-        attr_set = true;
-    }
+    static bool allowed[MAX_DEVICES] = {};
+    if (int rc = allow_lds((const void*)fn, lds, allowed)) return rc;
     SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + NWV - 1) / NWV)), dim3(64 * NWV), lds, s, feat, wp, out, out_f32,
               ms, counts, n_out_cap);
     return SC_OK;
