@@ -362,7 +362,7 @@ def main() -> int:
     st = dict(N=N, N_out=N_out, P=P, K3=K ** 3, cap=(sc.sc_hash_bytes(N) - 256) // 16, C_in=C_in, C_out=C_out,
               elem_bytes=d_feat.element_size())
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
     if os.path.exists(tpath):
         key = args.workload if args.table == "hash" else f"{args.workload}-{args.table}"
         traffic = json.load(open(tpath)).get(key, {}).get(dominant)
