@@ -81,7 +81,8 @@ typedef struct sc_counts {
 } sc_counts;
 
 /* ---- location table (Section III-C.1; the paper offers a dense array or a hash table, this
- * library uses an open-addressing hash table keyed on the packed 64-bit (b,x,y,z)) ---------- */
+ * library uses an open-addressing hash table keyed on the packed (b,x,y,z); sc_grid_* below is
+ * the dense array) ------------------------------------------------------------------------- */
 
 /* Bytes of the table for n keys: 16 bytes per slot plus a 256-byte header.  The capacity is a
  * power of two, at least 1024 slots and at least 8n (load factor <= 1/8); small tables are made
