@@ -287,7 +287,13 @@ def main() -> int:
                         if mode == "strided":
                             buf.kmap_build(d_coords, gstream, standalone=True)
                         else:
-                            buf.hash_build(d_coords, gstream)
+                            # a replay repeats the captured arguments, epoch included: the hash
+                            # table is captured with its full build (fill + insert); the dense
+                            # table's build is idempotent for one coordinate set and epoch
+                            if buf.grid_dims is None:
+                                sc.sc_hash_build(d_coords, buf.table, buf.counts, gstream)
+                            else:
+                                buf.hash_build(d_coords, gstream)
                             buf.kmap_build(d_coords, gstream)
                         buf.conv_fwd(d_feat, d_w, gstream)
             torch.cuda.synchronize()

@@ -112,6 +112,8 @@ int sc_hash_build(const int32_t* d_coords, int64_t n,
  * absent).  Tables above 64 MiB are filled all the same, with the capacity for n (measured
  * faster there: the fill leaves the table in the last-level cache for the probes that
  * follow), and then report like sc_hash_build.
+ * A captured HIP graph replays its arguments, the epoch among them: capture sc_hash_build, not
+ * this call, for a table that is rebuilt on every replay.
  * SC_EINVAL if epoch is outside 1..SC_HASH_EPOCH_MAX. */
 int sc_hash_rebuild(const int32_t* d_coords, int64_t n,
                     void* d_table, size_t table_bytes, int epoch,
