@@ -372,7 +372,12 @@ def main() -> int:
     if os.path.exists(tpath):
         key = args.workload if args.table == "hash" else f"{args.workload}-{args.table}"
         traffic = json.load(open(tpath)).get(key, {}).get(dominant)
-    if dominant in ("k_conv_mfma", "k_conv_f32"):
+    conv_bytes = algorithmic_bytes("k_conv_mfma", st)
+    conv_peak = PEAK_MFMA_TFLOPS if dtype != "f32" else PEAK_FP32_TFLOPS
+    # which roof a contraction of this shape is under: flops per algorithmic byte against the
+    # machine balance (peak flops / peak bytes).  32- and 64-channel layers sit under the HBM roof.
+    conv_under_hbm = flops / conv_bytes * PEAK_HBM_GBS * 1e9 < conv_peak * 1e12
+    if dominant in ("k_conv_mfma", "k_conv_f32") and not conv_under_hbm:
         # the contraction: flops of the pairs that exist against the matrix-core (or fp32 ALU) peak
         peak = PEAK_MFMA_TFLOPS if dominant == "k_conv_mfma" else PEAK_FP32_TFLOPS
         achieved = flops / avg_s / 1e12
@@ -386,6 +391,9 @@ def main() -> int:
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": (achieved / PEAK_HBM_GBS) if achieved else None,
                     "traffic": traffic, "avg_us": avg_s * 1e6, "launches_per_step": launches_per_step}
+        if dominant in ("k_conv_mfma", "k_conv_f32"):
+            roofline["flops_per_algorithmic_byte"] = flops / conv_bytes
+            roofline["tflops_active"] = flops / avg_s / 1e12
     per_kernel = {}
     for name in kernels:
         ab = algorithmic_bytes(name, st)
