@@ -200,6 +200,24 @@ int sc_kmap_build(const int32_t* d_coords, int64_t n,
                   void* d_scratch, size_t scratch_bytes,
                   sc_counts* d_counts, void* stream);
 
+/* sc_kmap_build for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same build with the scratch buffer
+ * taken from a fixed array inside the library (SC_NOALLOC_SCRATCH_BYTES of device memory per GPU
+ * the library runs on, held until the process ends) instead of d_scratch.  Every other argument,
+ * the results and the errors are those of sc_kmap_build; the call itself allocates nothing.
+ * SC_ECAP if sc_kmap_scratch_bytes(n, K, stride, mode) exceeds SC_NOALLOC_SCRATCH_BYTES (K ==
+ * stride layers: up to 65,536 input rows; submanifold layers need no scratch and are never
+ * refused for it).  All calls on one GPU share that one array: calls that overlap in time on the
+ * same GPU (different streams or host threads) race; calls on one stream are safe, and a call
+ * does not depend on what an earlier one left in the array. */
+#define SC_NOALLOC_SCRATCH_BYTES (16 << 20)
+int sc_kmap_build_noalloc(const int32_t* d_coords, int64_t n,
+                          const void* d_table,
+                          int K, int stride, int mode,
+                          int32_t* d_out_coords,
+                          void* d_kmap, size_t kmap_bytes,
+                          sc_counts* d_counts, void* stream);
+
 /* The submanifold kernel map (mode SC_SUBM, stride 1, K odd) from a dense location table built by
  * sc_grid_build(d_coords, n, ..., epoch): same blob, same meaning of every other argument as in
  * sc_kmap_build; needs no scratch buffer.  Every row reads its own cell: a row outside the box

@@ -30,7 +30,7 @@ SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_rebuild", "sc_hash_lookup"
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
            "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid",
-           "sc_conv_fwd_grid", "sc_conv_up_fwd"]
+           "sc_conv_fwd_grid", "sc_conv_up_fwd", "sc_kmap_build_noalloc"]
 
 
 class ScCounts(ctypes.Structure):
@@ -76,6 +76,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_kmap_bytes": (sz, [i64, i32, i32, i32]),
         "sc_kmap_scratch_bytes": (sz, [i64, i32, i32, i32]),
         "sc_kmap_build": (i32, [vp, i64, vp, i32, i32, i32, vp, vp, sz, vp, sz, vp, vp]),
+        "sc_kmap_build_noalloc": (i32, [vp, i64, vp, i32, i32, i32, vp, vp, sz, vp, vp]),
         "sc_kmap_transpose": (i32, [vp, i64, i32, i32, vp, vp, sz, vp]),
         "sc_conv_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "sc_conv_fwd": (i32, [vp, i64, vp, vp, i64, vp, sz, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
@@ -170,6 +171,14 @@ def sc_kmap_build(coords, table, K, stride, mode, out_coords, kmap, scratch, cou
                                 _ptr(kmap), kmap.numel() * kmap.element_size(),
                                 _ptr(scratch), 0 if scratch is None else scratch.numel() * scratch.element_size(),
                                 _ptr(counts), _stream(stream)), "sc_kmap_build")
+
+
+def sc_kmap_build_noalloc(coords, table, K, stride, mode, out_coords, kmap, counts, stream=None):
+    """sc_kmap_build with the scratch buffer inside the library (no device allocation anywhere)."""
+    n = coords.shape[0]
+    _check(load().sc_kmap_build_noalloc(_ptr(coords), n, _ptr(table), K, stride, MODES[mode], _ptr(out_coords),
+                                        _ptr(kmap), kmap.numel() * kmap.element_size(), _ptr(counts),
+                                        _stream(stream)), "sc_kmap_build_noalloc")
 
 
 def sc_grid_bytes(B: int, X: int, Y: int, Z: int) -> int:

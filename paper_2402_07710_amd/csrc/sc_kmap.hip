@@ -562,10 +562,10 @@ extern "C" size_t sc_kmap_scratch_bytes(int64_t n, int K, int stride, int mode) 
     return strided_scratch(nullptr, n).bytes;
 }
 
-extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
-                             int32_t* d_out_coords, void* d_kmap, size_t kmap_bytes, void* d_scratch,
-                             size_t scratch_bytes, sc_counts* d_counts, void* stream) {
-    if (!kmap_args_ok(n, K, stride, mode)) return SC_EINVAL;
+static int kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
+                      int32_t* d_out_coords, void* d_kmap, size_t kmap_bytes, void* d_scratch, size_t scratch_bytes,
+                      sc_counts* d_counts, void* stream) {
+    if (!kmap_args_ok(n, K, stride, mode) || mode == SC_INVERSE) return SC_EINVAL;   // inverse maps: sc_kmap_transpose
     if (d_kmap == nullptr || d_counts == nullptr || (n > 0 && d_coords == nullptr)) return SC_EINVAL;
     if (!aligned16(d_coords) || !aligned16(d_kmap) || !aligned16(d_counts) || !aligned16(d_out_coords) ||
         !aligned16(d_scratch) || !aligned16(d_table))
@@ -677,6 +677,48 @@ extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_t
     SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)L.tiles), dim3(256), 0, s,
               (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask, (const sc_counts*)d_counts, 0);
     return SC_OK;
+}
+
+extern "C" int sc_kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride, int mode,
+                             int32_t* d_out_coords, void* d_kmap, size_t kmap_bytes, void* d_scratch,
+                             size_t scratch_bytes, sc_counts* d_counts, void* stream) {
+    return kmap_build(d_coords, n, d_table, K, stride, mode, d_out_coords, d_kmap, kmap_bytes, d_scratch, scratch_bytes,
+                      d_counts, stream);
+}
+
+// ---- the same build for callers that cannot allocate ------------------------------------------
+// The scratch of a strided build (output-cell table, per-input slots, flag words, prefixes) lives
+// in one device array of the library instead of a caller's buffer.  Every device holds its own
+// copy of the array at its own address; the name below is only a host-side handle, so the
+// address is asked for once per device (with that device current) and that pointer is what the
+// kernels receive.  The build clears what it needs itself (k_strided_fill), so the contents a
+// previous call left behind do not matter; two calls that overlap on one device would race.
+static __device__ __align__(256) unsigned char scratch[SC_NOALLOC_SCRATCH_BYTES];
+
+static int noalloc_scratch(void** out) {
+    constexpr int MAX_DEVICES = 64;
+    static void* ptr[MAX_DEVICES] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return SC_EHIP;
+    if (ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SC_EHIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return SC_OK;
+}
+
+extern "C" int sc_kmap_build_noalloc(const int32_t* d_coords, int64_t n, const void* d_table, int K, int stride,
+                                     int mode, int32_t* d_out_coords, void* d_kmap, size_t kmap_bytes,
+                                     sc_counts* d_counts, void* stream) {
+    if (!kmap_args_ok(n, K, stride, mode) || mode == SC_INVERSE) return SC_EINVAL;
+    const size_t need = sc_kmap_scratch_bytes(n, K, stride, mode);
+    if (need > (size_t)SC_NOALLOC_SCRATCH_BYTES) return SC_ECAP;
+    void* p = nullptr;
+    if (int rc = noalloc_scratch(&p)) return rc;
+    return kmap_build(d_coords, n, d_table, K, stride, mode, d_out_coords, d_kmap, kmap_bytes, p,
+                      (size_t)SC_NOALLOC_SCRATCH_BYTES, d_counts, stream);
 }
 
 extern "C" int sc_kmap_transpose(const void* d_kmap, int64_t n, int K, int stride, const sc_counts* d_counts,
