@@ -2,7 +2,7 @@
  * sc.h — C ABI of the MI355X (gfx950) sparse 3-D convolution path.
  *
  * The three steps are the ones the paper gives for every sparse-convolution operator
- * (Section III-C: "create location table, create offset table, compute result"):
+ * (Section III-C: location table, offset table, result):
  *
  *     sc_hash_build   location table: coordinate -> input row        (Section III-C.1)
  *     (sc_hash_rebuild: the same into a table that is already initialised, without refilling it)
@@ -16,8 +16,11 @@
  * Conventions
  *   - Every pointer named d_* is DEVICE memory owned by the caller, 16-byte aligned, and only
  *     borrowed for the duration of the stream work the call enqueues.  Pointers named h_* are
- *     host memory.  The library allocates nothing on the device and keeps no state between
- *     calls (the optional timing aid at the end of this file aside).
+ *     host memory.  The library allocates nothing on the device (the measurement aids at the
+ *     end of this file aside).  State it keeps between calls: per device, which kernels have
+ *     been granted their large LDS allocation (set on first use) and the address of the array
+ *     behind sc_kmap_build_noalloc; process-wide, the samples of the optional timing aid.
+ *     None of it changes results.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls except
  *     sc_counts_read (and sc_profile_read) are asynchronous on that stream and never synchronise.
  *   - Every function returns an int status: SC_OK or a negative SC_E* code.  Argument errors
@@ -273,6 +276,29 @@ int sc_conv_fwd(const void* d_feat_in, int64_t n_map,
                 void* d_workspace, size_t workspace_bytes,
                 void* stream);
 
+/* The weights of a layer in the form sc_conv_fwd's kernels consume (Algorithm 2 indexes the
+ * weights per (offset, input channel, output channel); the matrix cores want them as operand
+ * tiles).  sc_conv_fwd re-lays the weights out on every call; a caller whose weights do not change
+ * from frame to frame packs them once and calls sc_conv_fwd_packed instead.
+ *   sc_conv_packed_bytes   bytes of the packed form (0 for an unsupported K / dtype)
+ *   sc_conv_weight_pack    d_weight [K^3][C_in][C_out] of dtype_in -> d_packed (packed_bytes >=
+ *                          sc_conv_packed_bytes(...)); asynchronous on `stream`.  The layout is
+ *                          private to the library and depends on (K, C_in, C_out, dtype_in); for
+ *                          SC_F32 it is a copy.  SC_EINVAL for channel counts sc_conv_fwd rejects.
+ *   sc_conv_fwd_packed     sc_conv_fwd with d_packed in place of d_weight and no workspace: same
+ *                          arguments otherwise, same results bit for bit. */
+size_t sc_conv_packed_bytes(int K, int C_in, int C_out, int dtype_in);
+int sc_conv_weight_pack(const void* d_weight, int K, int C_in, int C_out, int dtype_in,
+                        void* d_packed, size_t packed_bytes, void* stream);
+int sc_conv_fwd_packed(const void* d_feat_in, int64_t n_map,
+                       const void* d_packed,
+                       void* d_feat_out, int64_t n_out_cap,
+                       const void* d_kmap, size_t kmap_bytes,
+                       const sc_counts* d_counts,
+                       int K, int stride, int mode,
+                       int C_in, int C_out, int dtype_in, int dtype_out,
+                       void* stream);
+
 /* Fused form of the last two steps for 3x3x3 submanifold layers over a dense location table
  * (Section III-C.2 and III-C.3 in one pass): the convolution looks the 27 neighbours of its rows
  * up in the table built by sc_grid_build(d_coords, n, ..., epoch) itself, so no kernel map is
@@ -340,17 +366,25 @@ const char* sc_strerror(int status);
 /* Per-kernel timing for benchmarks.  sc_profile_enable(1) clears earlier samples and makes every
  * later call of this library attach a pair of HIP events to each kernel it launches (stamped with
  * the dispatch's own begin and end times); sc_profile_enable(0) stops that.  sc_profile_read
- * synchronises the device and fills up to max_entries entries (one per kernel that ran: name, number of launches, summed
- * duration in ms); it returns the number of entries written or a negative SC_E* code.  `name`
- * points to a static string.  This is process-wide state for single-threaded measurement code;
- * it is off by default. */
+ * synchronises the device and fills up to max_entries entries (one per kernel that ran: name,
+ * number of launches, summed and median duration in ms); it returns the number of entries written
+ * or a negative SC_E* code.  `name` points to a static string.  This is process-wide state for
+ * single-threaded measurement code (the only state the library keeps besides per-device launch
+ * attributes and the array of sc_kmap_build_noalloc); it is off by default. */
 typedef struct sc_profile_entry {
     const char* name;
     int64_t launches;
     double total_ms;
+    double median_ms;
 } sc_profile_entry;
 int sc_profile_enable(int enable);
 int sc_profile_read(sc_profile_entry* h_entries, int max_entries);
+
+/* Measured counterpart of the published matrix-core peak: runs a short loop of independent
+ * 16x16x32 fp16 multiplies with register operands on the current device (default stream,
+ * synchronises, allocates a few bytes for the duration of the call) and returns the sustained
+ * TFLOP/s in *h_tflops. */
+int sc_profile_mfma_peak(double* h_tflops);
 
 #ifdef __cplusplus
 }

@@ -30,7 +30,8 @@ SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_rebuild", "sc_hash_lookup"
            "sc_kmap_scratch_bytes", "sc_kmap_build", "sc_kmap_transpose", "sc_conv_workspace_bytes", "sc_conv_fwd",
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
            "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid",
-           "sc_conv_fwd_grid", "sc_conv_up_fwd", "sc_kmap_build_noalloc"]
+           "sc_conv_fwd_grid", "sc_conv_up_fwd", "sc_kmap_build_noalloc", "sc_profile_mfma_peak",
+           "sc_conv_packed_bytes", "sc_conv_weight_pack", "sc_conv_fwd_packed"]
 
 
 class ScCounts(ctypes.Structure):
@@ -42,7 +43,8 @@ COUNTS_BYTES = ctypes.sizeof(ScCounts)
 
 
 class ScProfileEntry(ctypes.Structure):
-    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double)]
+    _fields_ = [("name", ctypes.c_char_p), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
+                ("median_ms", ctypes.c_double)]
 
 
 class ScError(RuntimeError):
@@ -80,11 +82,15 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_kmap_transpose": (i32, [vp, i64, i32, i32, vp, vp, sz, vp]),
         "sc_conv_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "sc_conv_fwd": (i32, [vp, i64, vp, vp, i64, vp, sz, vp, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
+        "sc_conv_packed_bytes": (sz, [i32, i32, i32, i32]),
+        "sc_conv_weight_pack": (i32, [vp, i32, i32, i32, i32, vp, sz, vp]),
+        "sc_conv_fwd_packed": (i32, [vp, i64, vp, vp, i64, vp, sz, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "sc_counts_read": (i32, [vp, ctypes.POINTER(ScCounts), vp, i64, i32, i32, i32, vp]),
         "sc_kmap_export": (i32, [vp, i64, i32, i32, i32, ctypes.POINTER(ScCounts), vp, vp, vp, vp]),
         "sc_strerror": (ctypes.c_char_p, [i32]),
         "sc_profile_enable": (i32, [i32]),
         "sc_profile_read": (i32, [ctypes.POINTER(ScProfileEntry), i32]),
+        "sc_profile_mfma_peak": (i32, [ctypes.POINTER(ctypes.c_double)]),
         "sc_grid_bytes": (sz, [i32, i32, i32, i32]),
         "sc_grid_clear": (i32, [vp, sz, i32, i32, i32, i32, vp]),
         "sc_grid_build": (i32, [vp, i64, vp, sz, i32, i32, i32, i32, ctypes.c_uint32, vp, vp]),
@@ -248,6 +254,38 @@ def sc_conv_fwd(feat_in, weight, feat_out, kmap, counts, K, stride, mode, worksp
                               _stream(stream)), "sc_conv_fwd")
 
 
+def sc_conv_packed_bytes(K: int, C_in: int, C_out: int, dtype) -> int:
+    return load().sc_conv_packed_bytes(K, C_in, C_out, DTYPES[dtype])
+
+
+def sc_conv_weight_pack(weight, K, packed=None, stream=None):
+    """weight [K^3, C_in, C_out] -> the packed form sc_conv_fwd_packed takes (a uint8 tensor; allocated
+    here unless `packed` is given)."""
+    C_in, C_out = weight.shape[1], weight.shape[2]
+    if tuple(weight.shape) != (K ** 3, C_in, C_out):
+        raise ValueError("weight must be [K^3, C_in, C_out]")
+    if packed is None:
+        packed = torch.empty(max(sc_conv_packed_bytes(K, C_in, C_out, weight.dtype), 16), dtype=torch.uint8,
+                             device=weight.device)
+    _check(load().sc_conv_weight_pack(_ptr(weight), K, C_in, C_out, DTYPES[weight.dtype], _ptr(packed),
+                                      packed.numel() * packed.element_size(), _stream(stream)), "sc_conv_weight_pack")
+    return packed
+
+
+def sc_conv_fwd_packed(feat_in, packed, C_out, feat_out, kmap, counts, K, stride, mode, stream=None, n_map=None):
+    """sc_conv_fwd with weights packed by sc_conv_weight_pack."""
+    n_in, C_in = feat_in.shape
+    n_out_cap = feat_out.shape[0]
+    if n_map is None:
+        n_map = n_in
+    if feat_out.shape[1] != C_out:
+        raise ValueError("feat_out must have C_out columns")
+    _check(load().sc_conv_fwd_packed(_ptr(feat_in), n_map, _ptr(packed), _ptr(feat_out), n_out_cap, _ptr(kmap),
+                                     kmap.numel() * kmap.element_size(), _ptr(counts), K, stride, MODES[mode],
+                                     C_in, C_out, DTYPES[feat_in.dtype], DTYPES[feat_out.dtype], _stream(stream)),
+           "sc_conv_fwd_packed")
+
+
 def sc_counts_read(counts, kmap=None, n=0, K=1, stride=1, mode="subm", stream=None, check=True) -> ScCounts:
     h = ScCounts()
     rc = load().sc_counts_read(_ptr(counts), ctypes.byref(h), _ptr(kmap), n, K, stride, MODES[mode], _stream(stream))
@@ -273,12 +311,20 @@ def sc_profile_enable(enable: bool):
 
 
 def sc_profile_read() -> dict:
-    """{kernel name: (launches, total ms)} for the kernels that ran since sc_profile_enable(True)."""
+    """{kernel name: (launches, total ms, median ms)} for the kernels that ran since sc_profile_enable(True)."""
     arr = (ScProfileEntry * 32)()
     n = load().sc_profile_read(arr, 32)
     if n < 0:
         raise ScError(n, "sc_profile_read")
-    return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].total_ms)) for i in range(n)}
+    return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].total_ms), float(arr[i].median_ms))
+            for i in range(n)}
+
+
+def sc_profile_mfma_peak() -> float:
+    """Sustained TFLOP/s of a register-operand fp16 MFMA loop on the current device."""
+    v = ctypes.c_double(0.0)
+    _check(load().sc_profile_mfma_peak(ctypes.byref(v)), "sc_profile_mfma_peak")
+    return v.value
 
 
 # ---- buffers for one layer -------------------------------------------------------------------
@@ -349,6 +395,11 @@ class LayerBuffers:
     def conv_fwd(self, feat_in, weight, stream=None):
         sc_conv_fwd(feat_in, weight, self.feat_out, self.kmap, self.counts, self.K, self.stride, self.mode,
                     self.workspace, stream)
+
+    def conv_fwd_packed(self, feat_in, packed, stream=None):
+        """The convolution with weights packed once by sc_conv_weight_pack."""
+        sc_conv_fwd_packed(feat_in, packed, self.C_out, self.feat_out, self.kmap, self.counts, self.K, self.stride,
+                           self.mode, stream)
 
     def layer_fused(self, coords, feat_in, weight, stream=None):
         """Dense table + fused look-up and convolution (3x3x3 submanifold layers, grid_dims given)."""

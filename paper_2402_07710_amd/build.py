@@ -17,6 +17,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # "#pragma unroll" gives up above a size limit; the convolution kernels unroll their 27 offsets
+    # in full on purpose (register arrays indexed by the offset must stay in registers)
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
     "-Wall", "-Wno-unused-command-line-argument", "-Wno-option-ignored",
 ]

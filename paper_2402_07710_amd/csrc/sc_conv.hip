@@ -22,8 +22,15 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// W [K3][C_in][C_out] (16-bit elements) -> MFMA A-operand tiles of W[k]^T:
-// wp[((k*CB + cb)*KS + ks)*64 + lane] holds W[k][ks*32 + 8*(lane/16) + j][cb*16 + lane%16], j = 0..7
+// Packed weights: W [K3][C_in][C_out] (16-bit elements) as MFMA A-operand tiles of W[k]^T.  A tile
+// is 64 lanes x 16 bytes: lane l of tile (k, cb, ks) holds W[k][ks*32 + 8*(l/16) + j][cb*16 + l%16],
+// j = 0..7.  Inside one offset k the tiles are ordered by 64-channel half of C_in first, then
+// output block, then 32-channel slice of the half, so the tiles a kernel needs for one half of the
+// input channels are one contiguous piece: tile number wtile(KS, CB, cb, ks) below (for C_in = 32
+// there is one slice and the order is just cb).
+__host__ __device__ constexpr int wtile(int KS, int CB, int cb, int ks) {
+    return KS == 1 ? cb : ((ks >> 1) * CB + cb) * 2 + (ks & 1);
+}
 __global__ void __launch_bounds__(256)
 k_weight_pack(const uint16_t* __restrict__ w, uint4* __restrict__ wp, int K3, int C_in, int C_out) {
     const int KS = C_in / 32, CB = C_out / 16;
@@ -42,7 +49,7 @@ k_weight_pack(const uint16_t* __restrict__ w, uint4* __restrict__ wp, int K3, in
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         v[j] = (uint32_t)src[(int64_t)(2 * j) * C_out] | ((uint32_t)src[(int64_t)(2 * j + 1) * C_out] << 16);
-    wp[t] = make_uint4(v[0], v[1], v[2], v[3]);
+    wp[((int64_t)k * CB * KS + wtile(KS, CB, cb, ks)) * 64 + lane] = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 // Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits until every
@@ -100,7 +107,7 @@ __device__ inline void store_acc(void* __restrict__ out, int out_f32, int64_t ro
 // coarse rows, read in place; entry k of a row's table column names the fine row that receives
 // row . W[k].  Every fine row has exactly one parent, so results are stored, not accumulated, and
 // nothing needs to be transposed first.
-template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0>
+template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0, int WPACKED = 0>
 __global__ void __launch_bounds__(256 * NT)
 k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw, void* __restrict__ out, int out_f32,
               const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
@@ -157,7 +164,10 @@ k_conv_rows16(const uint16_t* __restrict__ feat, const uint4* __restrict__ wraw,
     // weights -> LDS as operand tiles (every thread helps, also wavefronts without rows): the
     // thread that fills (tile, lane) reads its 8 input channels of one output channel (2-byte
     // loads, 128 contiguous bytes per wavefront) and writes them as one 16-byte LDS store
-    {
+    if constexpr (WPACKED) {
+        // the caller packed the weights once (sc_conv_weight_pack): the tiles are copied as they are
+        for (int i = threadIdx.x; i < K3 * CB * KS * 64; i += 256 * NT) w_lds[i] = wraw[i];
+    } else {
         const uint16_t* w16 = reinterpret_cast<const uint16_t*>(wraw);
         for (int i = threadIdx.x; i < K3 * CB * KS * 64; i += 256 * NT) {
             const int ln = i & 63;
@@ -417,7 +427,7 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
             for (int c0 = 0; c0 < CB; c0 += CBG) {
                 uint4 a[CBG];
 #pragma unroll
-                for (int c = 0; c < CBG; ++c) a[c] = wk[((c0 + c) * KS + ks) * 64];
+                for (int c = 0; c < CBG; ++c) a[c] = wk[wtile(KS, CB, c0 + c, ks) * 64];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     if ((mg[g] >> k) & 1u) {
@@ -503,7 +513,7 @@ k_conv_rows16_any(const uint16_t* __restrict__ feat, const uint4* __restrict__ w
                 if (cb < CB) {
 #pragma unroll
                     for (int ks = 0; ks < KS_MAX; ++ks)
-                        if (ks < KS) acc[cb] = mfma16x16x32<DT>(wk[(cb * KS + ks) * 64], fb[ks], acc[cb]);
+                        if (ks < KS) acc[cb] = mfma16x16x32<DT>(wk[wtile(KS, CB, cb, ks) * 64], fb[ks], acc[cb]);
                 }
             }
         }
@@ -655,10 +665,10 @@ static int allow_lds(const void* fn, size_t lds, bool (&done)[MAX_DEVICES]) {
     return SC_OK;
 }
 
-template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0>
+template <int DT, int K3, int KS, int CB, int NT, int FUSED, int UP = 0, int WPACKED = 0>
 static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_rows16<DT, K3, KS, CB, NT, FUSED, UP>;
+    auto fn = k_conv_rows16<DT, K3, KS, CB, NT, FUSED, UP, WPACKED>;
     const size_t lds = (size_t)K3 * CB * KS * 64 * sizeof(uint4);
     static bool allowed[MAX_DEVICES] = {};  // per instantiation
     if (int rc = allow_lds((const void*)fn, lds, allowed)) return rc;
@@ -667,14 +677,22 @@ static int launch_rows16(int64_t tiles, hipStream_t s, const uint16_t* feat, con
     return SC_OK;
 }
 
-// Shapes whose packed weights fit in LDS as a whole.
-template <int DT, int FUSED>
+// Shapes whose packed weights fit in LDS as a whole.  The resident kernel's LDS layout of the
+// weights is the packed layout itself (tile (k, cb, ks) at ((k CB + cb) KS + ks): one 64-channel
+// half at most), so packed weights are copied and raw ones re-laid out on the way in.
+static bool resident_shape(int K3, int C_in, int C_out, bool fused) {
+    if (K3 == 27 && C_in == 32 && C_out == 32) return true;
+    if (fused) return false;
+    return K3 == 8 && ((C_in == 32 && C_out == 64) || (C_in == 32 && C_out == 32) || (C_in == 64 && C_out == 64) ||
+                       (C_in == 64 && C_out == 32));
+}
+template <int DT, int FUSED, int WPACKED>
 static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
                            const uint4* wp, void* out, int out_f32, const MapSource& ms, const int64_t* counts,
                            int64_t n_out_cap, bool* handled) {
     *handled = true;
 #define SC_ROWS16(K3V, KSV, CBV, NTV) \
-    return launch_rows16<DT, K3V, KSV, CBV, NTV, FUSED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
+    return launch_rows16<DT, K3V, KSV, CBV, NTV, FUSED, 0, WPACKED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
     // four tiles per workgroup once every CU still gets a workgroup: the weights are re-laid out
     // half as often and no CU hosts two workgroups while another hosts one (cfg2: 11.9 -> 10.6 us)
     if (K3 == 27 && C_in == 32 && C_out == 32 && tiles >= 512) SC_ROWS16(27, 1, 2, 4);
@@ -746,30 +764,59 @@ static bool mfma_channels_ok(int C_in, int C_out) {
     return (C_in == 32 || C_in == 64 || C_in == 128 || C_in == 256) && C_out >= 16 && C_out <= 256 && C_out % 16 == 0;
 }
 
-// The 16-bit layer shapes with a dedicated kernel: small layers take their weights straight from
-// d_weight (re-laid out into LDS by the kernel), the others from the packed copy this makes in
-// the workspace.  *handled = false if the shape has no dedicated kernel.
-template <int FUSED>
-static int conv_16bit(int dtype_in, int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const void* d_feat_in,
-                      const void* d_weight, void* d_workspace, void* d_feat_out, int out_f32, const MapSource& ms,
-                      const int64_t* n_out_ptr, int64_t n_out_cap, bool* handled) {
-    const uint16_t* feat = (const uint16_t*)d_feat_in;
-    int rc = dtype_in == SC_F16 ? launch_resident<SC_F16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
-                                                                 d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled)
-                                : launch_resident<SC_BF16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
-                                                                  d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled);
-    if (*handled || rc != SC_OK) return rc;
-    const bool stream_shape = K3 == 27 && ((C_in == 64 && C_out == 64) || (C_in == 128 && C_out == 128) ||
-                                           (C_in == 32 && C_out == 64) || (C_in == 64 && C_out == 128));
-    const bool stream_shape8 = !FUSED && K3 == 8 && ((C_in == 64 && C_out == 128) || (C_in == 128 && C_out == 128));
-    if (!stream_shape && !stream_shape8) return SC_OK;
+// Packed form of 16-bit weights [K3][C_in][C_out] for sc_conv_fwd's kernels (operand tiles, see k_weight_pack).
+static int pack_weights(int K3, int C_in, int C_out, const void* d_weight, void* d_packed, hipStream_t s) {
     const int64_t pack_threads = (int64_t)K3 * (C_out / 16) * (C_in / 32) * 64;
     SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
-              (const uint16_t*)d_weight, (uint4*)d_workspace, K3, C_in, C_out);
-    return dtype_in == SC_F16 ? launch_streamed<SC_F16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_workspace,
-                                                               d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled)
-                              : launch_streamed<SC_BF16, FUSED>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_workspace,
-                                                                d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, handled);
+              (const uint16_t*)d_weight, (uint4*)d_packed, K3, C_in, C_out);
+    return SC_OK;
+}
+
+// A 16-bit layer.  `packed`: d_weight is what sc_conv_weight_pack made; otherwise the raw weights,
+// which the resident kernels re-lay out themselves and the others have packed into the workspace
+// first.  FUSED (dense table, no map) always takes raw weights.
+template <int FUSED>
+static int conv_16bit(int dtype_in, int K3, int mw, int C_in, int C_out, int64_t tiles, hipStream_t s, const void* d_feat_in,
+                      const void* d_weight, bool packed, void* d_workspace, void* d_feat_out,
+                      int out_f32, const MapSource& ms, const int64_t* n_out_ptr, int64_t n_out_cap) {
+    const uint16_t* feat = (const uint16_t*)d_feat_in;
+    bool handled = false;
+    int rc;
+    if (resident_shape(K3, C_in, C_out, FUSED)) {
+        if (packed)
+            rc = dtype_in == SC_F16 ? launch_resident<SC_F16, FUSED, 1>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
+                                                                       d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, &handled)
+                                    : launch_resident<SC_BF16, FUSED, 1>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
+                                                                        d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, &handled);
+        else
+            rc = dtype_in == SC_F16 ? launch_resident<SC_F16, FUSED, 0>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
+                                                                       d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, &handled)
+                                    : launch_resident<SC_BF16, FUSED, 0>(K3, C_in, C_out, tiles, s, feat, (const uint4*)d_weight,
+                                                                        d_feat_out, out_f32, ms, n_out_ptr, n_out_cap, &handled);
+        return rc;
+    }
+    const bool stream_shape = (K3 == 27 && ((C_in == 64 && C_out == 64) || (C_in == 128 && C_out == 128) ||
+                                            (C_in == 32 && C_out == 64) || (C_in == 64 && C_out == 128))) ||
+                              (!FUSED && K3 == 8 && ((C_in == 64 && C_out == 128) || (C_in == 128 && C_out == 128)));
+    if (FUSED && !stream_shape) return SC_EINVAL;     // no fused kernel for this shape: use the three calls
+    const uint4* wp = (const uint4*)d_weight;
+    if (!packed) {
+        if (int prc = pack_weights(K3, C_in, C_out, d_weight, d_workspace, s)) return prc;
+        wp = (const uint4*)d_workspace;
+    }
+    rc = dtype_in == SC_F16 ? launch_streamed<SC_F16, FUSED>(K3, C_in, C_out, tiles, s, feat, wp, d_feat_out, out_f32, ms,
+                                                            n_out_ptr, n_out_cap, &handled)
+                            : launch_streamed<SC_BF16, FUSED>(K3, C_in, C_out, tiles, s, feat, wp, d_feat_out, out_f32, ms,
+                                                             n_out_ptr, n_out_cap, &handled);
+    if (handled || rc != SC_OK) return rc;
+    if (FUSED) return SC_EINVAL;
+    if (dtype_in == SC_F16)
+        SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_F16>, dim3((unsigned)tiles), dim3(256), 0, s, feat, wp, d_feat_out, out_f32,
+                  ms.gmask, ms.nbr, K3, mw, C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
+    else
+        SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_BF16>, dim3((unsigned)tiles), dim3(256), 0, s, feat, wp, d_feat_out, out_f32,
+                  ms.gmask, ms.nbr, K3, mw, C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
+    return SC_OK;
 }
 
 }  // namespace sc
@@ -782,10 +829,10 @@ extern "C" size_t sc_conv_workspace_bytes(int K, int C_in, int C_out, int dtype_
     return align_up((size_t)K * K * K * C_in * C_out * 2, 256);
 }
 
-extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_weight, void* d_feat_out,
-                           int64_t n_out_cap, const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts, int K,
-                           int stride, int mode, int C_in, int C_out, int dtype_in, int dtype_out, void* d_workspace,
-                           size_t workspace_bytes, void* stream) {
+static int conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_weight, bool packed, void* d_feat_out,
+                    int64_t n_out_cap, const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts, int K, int stride,
+                    int mode, int C_in, int C_out, int dtype_in, int dtype_out, void* d_workspace, size_t workspace_bytes,
+                    void* stream) {
     if (n_map < 0 || n_map > SC_N_MAX || n_out_cap < 0 || K < 1 || K > SC_K_MAX || C_in < 1 || C_out < 1) return SC_EINVAL;
     if (d_weight == nullptr || d_kmap == nullptr || d_counts == nullptr) return SC_EINVAL;
     if ((n_map > 0 && d_feat_in == nullptr) || (n_out_cap > 0 && d_feat_out == nullptr)) return SC_EINVAL;
@@ -807,7 +854,7 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
     const int32_t* nbr = (const int32_t*)((const char*)d_kmap + L.off_nbr);
     hipStream_t s = (hipStream_t)stream;
 
-    if (dtype_in == SC_F32) {
+    if (dtype_in == SC_F32) {           // fp32 weights are used as they are: packed == raw
         if (C_out > 256) return SC_EINVAL;
         if (L.K3 <= 32 && C_in % 16 == 0 && C_in <= 64 && C_out % 16 == 0 && C_out <= 64) {
 #define SC_F32_SMALL(CI, CBV)                                                                                         \
@@ -828,28 +875,53 @@ extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_w
     }
 
     if (!mfma_channels_ok(C_in, C_out)) return SC_EINVAL;
-    const size_t need = sc_conv_workspace_bytes(K, C_in, C_out, dtype_in);
-    if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
-    const int out_f32 = dtype_out == SC_F32;
-    {
-        bool handled = false;
-        const MapSource ms{gmask, nbr, nullptr, nullptr, GridDims{0, 0, 0, 0}, 0u};
-        const int rc = conv_16bit<0>(dtype_in, L.K3, C_in, C_out, tiles, s, d_feat_in, d_weight, d_workspace, d_feat_out,
-                                     out_f32, ms, n_out_ptr, n_out_cap, &handled);
-        if (handled || rc != SC_OK) return rc;
+    if (!packed) {
+        const size_t need = sc_conv_workspace_bytes(K, C_in, C_out, dtype_in);
+        if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
     }
-    const int64_t pack_threads = (int64_t)L.K3 * (C_out / 16) * (C_in / 32) * 64;
-    SC_LAUNCH(KID_WEIGHT_PACK, k_weight_pack, dim3((unsigned)((pack_threads + 255) / 256)), dim3(256), 0, s,
-              (const uint16_t*)d_weight, (uint4*)d_workspace, L.K3, C_in, C_out);
-    if (dtype_in == SC_F16)
-        SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_F16>, dim3((unsigned)tiles), dim3(256), 0, s,
-                  (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
-                  C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
-    else
-        SC_LAUNCH(KID_CONV_MFMA, k_conv_rows16_any<SC_BF16>, dim3((unsigned)tiles), dim3(256), 0, s,
-                  (const uint16_t*)d_feat_in, (const uint4*)d_workspace, d_feat_out, out_f32, gmask, nbr, L.K3, L.mw,
-                  C_in / 32, C_out / 16, n_out_ptr, n_out_cap);
-    return SC_OK;
+    const MapSource ms{gmask, nbr, nullptr, nullptr, GridDims{0, 0, 0, 0}, 0u};
+    return conv_16bit<0>(dtype_in, L.K3, L.mw, C_in, C_out, tiles, s, d_feat_in, d_weight, packed, d_workspace,
+                         d_feat_out, dtype_out == SC_F32, ms, n_out_ptr, n_out_cap);
+}
+
+extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_weight, void* d_feat_out,
+                           int64_t n_out_cap, const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts, int K,
+                           int stride, int mode, int C_in, int C_out, int dtype_in, int dtype_out, void* d_workspace,
+                           size_t workspace_bytes, void* stream) {
+    return conv_fwd(d_feat_in, n_map, d_weight, false, d_feat_out, n_out_cap, d_kmap, kmap_bytes, d_counts, K, stride, mode,
+                    C_in, C_out, dtype_in, dtype_out, d_workspace, workspace_bytes, stream);
+}
+
+extern "C" int sc_conv_fwd_packed(const void* d_feat_in, int64_t n_map, const void* d_packed, void* d_feat_out,
+                                  int64_t n_out_cap, const void* d_kmap, size_t kmap_bytes, const sc_counts* d_counts,
+                                  int K, int stride, int mode, int C_in, int C_out, int dtype_in, int dtype_out,
+                                  void* stream) {
+    return conv_fwd(d_feat_in, n_map, d_packed, true, d_feat_out, n_out_cap, d_kmap, kmap_bytes, d_counts, K, stride, mode,
+                    C_in, C_out, dtype_in, dtype_out, nullptr, 0, stream);
+}
+
+extern "C" size_t sc_conv_packed_bytes(int K, int C_in, int C_out, int dtype_in) {
+    if (K < 1 || K > SC_K_MAX || C_in < 1 || C_out < 1) return 0;
+    if (dtype_in == SC_F32) return align_up((size_t)K * K * K * C_in * C_out * 4, 256);
+    if (dtype_in != SC_F16 && dtype_in != SC_BF16) return 0;
+    return align_up((size_t)K * K * K * C_in * C_out * 2, 256);
+}
+
+extern "C" int sc_conv_weight_pack(const void* d_weight, int K, int C_in, int C_out, int dtype_in, void* d_packed,
+                                   size_t packed_bytes, void* stream) {
+    const size_t need = sc_conv_packed_bytes(K, C_in, C_out, dtype_in);
+    if (need == 0 || d_weight == nullptr || d_packed == nullptr || !aligned16(d_weight) || !aligned16(d_packed))
+        return SC_EINVAL;
+    if (packed_bytes < need) return SC_ECAP;
+    hipStream_t s = (hipStream_t)stream;
+    const int K3 = K * K * K;
+    if (dtype_in == SC_F32) {
+        if (C_out > 256) return SC_EINVAL;
+        return hipMemcpyAsync(d_packed, d_weight, (size_t)K3 * C_in * C_out * 4, hipMemcpyDeviceToDevice, s) == hipSuccess
+                   ? SC_OK : SC_EHIP;
+    }
+    if (!mfma_channels_ok(C_in, C_out)) return SC_EINVAL;
+    return pack_weights(K3, C_in, C_out, d_weight, d_packed, s);
 }
 
 extern "C" int sc_conv_up_fwd(const void* d_feat_coarse, int64_t n_map, const void* d_weight, void* d_feat_fine,
@@ -900,9 +972,7 @@ extern "C" int sc_conv_fwd_grid(const void* d_feat_in, const int32_t* d_coords, 
     if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
     if (n == 0) return SC_OK;
     const MapSource ms{nullptr, nullptr, (const int4*)d_coords, (const unsigned long long*)d_grid, GridDims{B, X, Y, Z}, epoch};
-    bool handled = false;
-    const int rc = conv_16bit<1>(dtype_in, 27, C_in, C_out, (n + TILE - 1) / TILE, (hipStream_t)stream, d_feat_in, d_weight,
-                                 d_workspace, d_feat_out, dtype_out == SC_F32, ms, nullptr, n, &handled);
-    if (rc != SC_OK) return rc;
-    return handled ? SC_OK : SC_EINVAL;        // no fused kernel for this shape: use the three calls
+    if (!mfma_channels_ok(C_in, C_out)) return SC_EINVAL;
+    return conv_16bit<1>(dtype_in, 27, 1, C_in, C_out, (n + TILE - 1) / TILE, (hipStream_t)stream, d_feat_in, d_weight,
+                         false, d_workspace, d_feat_out, dtype_out == SC_F32, ms, nullptr, n);
 }
