@@ -359,6 +359,11 @@ int sc_kmap_export(const void* d_kmap, int64_t n, int K, int stride, int mode,
 int sc_hash_lookup(const void* d_table, int64_t n_table,
                    const int32_t* d_query, int64_t n_query, int32_t* d_rows, void* stream);
 
+/* Host-side inspection aid: the slot (0 .. capacity-1) at which a table sized for n keys looks for
+ * coordinate (b,x,y,z) on its attempt-th try (0 = first); -1 outside the key domain.  Pure
+ * arithmetic, no device work; lets tests examine the probe sequence. */
+int64_t sc_hash_probe_slot(int32_t b, int32_t x, int32_t y, int32_t z, uint32_t attempt, int64_t n);
+
 const char* sc_strerror(int status);
 
 /* ---- measurement aid (not part of the paper's method) -------------------------------------- */

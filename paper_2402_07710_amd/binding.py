@@ -31,7 +31,7 @@ SYMBOLS = ["sc_hash_bytes", "sc_hash_build", "sc_hash_rebuild", "sc_hash_lookup"
            "sc_counts_read", "sc_kmap_export", "sc_strerror", "sc_profile_enable", "sc_profile_read",
            "sc_grid_bytes", "sc_grid_clear", "sc_grid_build", "sc_grid_lookup", "sc_kmap_build_grid",
            "sc_conv_fwd_grid", "sc_conv_up_fwd", "sc_kmap_build_noalloc", "sc_profile_mfma_peak",
-           "sc_conv_packed_bytes", "sc_conv_weight_pack", "sc_conv_fwd_packed"]
+           "sc_conv_packed_bytes", "sc_conv_weight_pack", "sc_conv_fwd_packed", "sc_hash_probe_slot"]
 
 
 class ScCounts(ctypes.Structure):
@@ -88,6 +88,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "sc_counts_read": (i32, [vp, ctypes.POINTER(ScCounts), vp, i64, i32, i32, i32, vp]),
         "sc_kmap_export": (i32, [vp, i64, i32, i32, i32, ctypes.POINTER(ScCounts), vp, vp, vp, vp]),
         "sc_strerror": (ctypes.c_char_p, [i32]),
+        "sc_hash_probe_slot": (i64, [i32, i32, i32, i32, ctypes.c_uint32, i64]),
         "sc_profile_enable": (i32, [i32]),
         "sc_profile_read": (i32, [ctypes.POINTER(ScProfileEntry), i32]),
         "sc_profile_mfma_peak": (i32, [ctypes.POINTER(ctypes.c_double)]),

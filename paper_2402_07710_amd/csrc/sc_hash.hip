@@ -59,8 +59,19 @@ k_hash_insert(const int4* __restrict__ coords, int64_t n, uint4* slots, uint32_t
         }
     }
     auto report = [&](int code) {
-        if (FRESH) latch_status(counts, code);
-        else atomicMax(&th->err_tag, (epoch << 8) | (uint32_t)(-code));
+        if (FRESH) {
+            latch_status(counts, code);
+            return;
+        }
+        // the tag of another epoch is stale whatever its value (epochs need not be used in rising
+        // order): replace it; within this epoch keep the largest code
+        const uint32_t mine_tag = (epoch << 8) | (uint32_t)(-code);
+        uint32_t seen = th->err_tag;
+        while ((seen >> 8) != epoch || seen < mine_tag) {
+            const uint32_t prev = atomicCAS(&th->err_tag, seen, mine_tag);
+            if (prev == seen) break;
+            seen = prev;
+        }
     };
     if (i >= n) return;
     if (!FRESH && (uint64_t)n * 4 > (uint64_t)mask + 1) {      // more rows than this table was made for
@@ -177,6 +188,11 @@ extern "C" int sc_hash_lookup(const void* d_table, int64_t n_table, const int32_
     SC_LAUNCH(KID_HASH_LOOKUP, k_hash_lookup, dim3((unsigned)((n_query + 255) / 256)), dim3(256), 0, s,
               (const uint4*)t.slots, (const TableHeader*)t.hdr, (const int4*)d_query, n_query, d_rows);
     return SC_OK;
+}
+
+extern "C" int64_t sc_hash_probe_slot(int32_t b, int32_t x, int32_t y, int32_t z, uint32_t attempt, int64_t n) {
+    if (n < 0 || n > SC_N_MAX || !in_domain4(b, x, y, z)) return -1;
+    return (int64_t)probe_slot(pack_key(b, x, y, z), attempt, (uint32_t)(table_capacity(n) - 1));
 }
 
 extern "C" const char* sc_strerror(int status) {

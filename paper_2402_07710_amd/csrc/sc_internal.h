@@ -36,7 +36,7 @@ __host__ __device__ inline bool in_domain4(int b, int x, int y, int z) {
 
 // Probe sequence of a key.  The table is cut into regions of 64 slots; a 4x4x4 block of cells
 // owns one region per attempt t (a hash of the block's coordinates and t) and a cell sits at its
-// own place inside the region (its 6 low coordinate bits).  Cells of one block therefore never
+// own place inside the region (its 6 low coordinate bits, turned by 6 bits of the same hash).  Cells of one block therefore never
 // collide with each other, the 27 neighbours of a voxel fall into at most 8 regions, and voxels
 // that are close in space read the same cache lines of the table.  After REHASH_MAX attempts the
 // sequence continues linearly, so it visits every slot and always ends at an empty one.
@@ -53,7 +53,12 @@ __host__ __device__ inline uint32_t probe_slot(uint64_t key, uint32_t t, uint32_
     const uint32_t lo = (uint32_t)key & 0xfffcfffcu;                  // y >> 2, z >> 2
     const uint32_t local = (((uint32_t)(key >> 32) & 3u) << 4) | (((uint32_t)(key >> 16) & 3u) << 2) | ((uint32_t)key & 3u);
     const uint32_t tt = t < REHASH_MAX ? t : REHASH_MAX - 1;
-    const uint32_t slot = ((mix_block(hi, lo, tt) << 6) | local) + (t - tt);
+    // the place inside the region is turned by six more bits of the block's hash: one turn for the
+    // whole block and attempt, so its cells still never collide with each other, but voxel sets
+    // on a coarse lattice (every coordinate a multiple of 2 or 4, as after down-sampling at the
+    // original scale) no longer all ask for the same few places of every region
+    const uint32_t h = mix_block(hi, lo, tt);
+    const uint32_t slot = ((h << 6) | (local ^ (h >> 26))) + (t - tt);
     return slot & mask;
 }
 

@@ -278,16 +278,60 @@ k_scan_blocks(const int32_t* __restrict__ block_sum, int32_t* __restrict__ block
     if (threadIdx.x == 0) counts->n_out = carry_s;
 }
 
+// Exclusive prefix of the per-block counts, computed by every workgroup for itself into LDS (the
+// counts of a few hundred to a few thousand 1024-input blocks: cheaper than a kernel of its own,
+// which is one workgroup long).  Returns the total.  All threads of the workgroup call it.
+constexpr int SCAN_IN_PAIRS_MAX = 4096;              // blocks (4 M inputs); more: k_scan_blocks
+__device__ inline int32_t block_prefix_to_lds(const int32_t* __restrict__ block_sum, int nblk, int32_t* prefix_s,
+                                              int32_t* wave_s) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int per = (nblk + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int lo = threadIdx.x * per, hi = lo + per < nblk ? lo + per : nblk;
+    int32_t sum = 0;
+    for (int i = lo; i < hi; ++i) sum += block_sum[i];
+    int32_t incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int32_t v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    if (lane == 63) wave_s[wave] = incl;
+    __syncthreads();
+    int32_t before = 0, total = 0;
+    for (int w = 0; w < nwaves; ++w) {
+        if (w < wave) before += wave_s[w];
+        total += wave_s[w];
+    }
+    int32_t run = before + incl - sum;
+    for (int i = lo; i < hi; ++i) {
+        prefix_s[i] = run;
+        run += block_sum[i];
+    }
+    __syncthreads();
+    return total;
+}
+
 // Every input finds its output row (rank of its cell's first input among all first inputs),
 // its in-cell offset (eq. 3) and kernel offset (eq. 5), and records itself in the offset table.
+// SCAN: the prefix of the block counts is made here (block_prefix is then unused) and workgroup 0
+// writes the number of output rows.
+template <int SCAN>
 __global__ void __launch_bounds__(256)
 k_strided_pairs(const int4* __restrict__ coords, int64_t n, int s, int K3,
                 const int32_t* __restrict__ slot_of, const uint4* __restrict__ oslots,
                 const uint64_t* __restrict__ flagword, const int32_t* __restrict__ word_prefix,
-                const int32_t* __restrict__ block_prefix, int32_t* __restrict__ nbr,
-                int4* __restrict__ out_coords, KmapHeader* hdr, KmapHeader hdr_value) {
+                const int32_t* __restrict__ block_prefix, const int32_t* __restrict__ block_sum, int nblk,
+                int32_t* __restrict__ nbr, int4* __restrict__ out_coords, sc_counts* counts, KmapHeader* hdr,
+                KmapHeader hdr_value) {
+    __shared__ int32_t prefix_s[SCAN ? SCAN_IN_PAIRS_MAX : 1];
+    __shared__ int32_t wave_s[4];
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) *hdr = hdr_value;
+    if constexpr (SCAN) {
+        const int32_t total = block_prefix_to_lds(block_sum, nblk, prefix_s, wave_s);
+        if (i == 0) counts->n_out = total;
+        block_prefix = prefix_s;
+    }
     if (i >= n) return;
     const int32_t sl = slot_of[i];
     if (sl < 0) return;
@@ -668,12 +712,19 @@ static int kmap_build(const int32_t* d_coords, int64_t n, const void* d_table, i
               sc_.oslots, sc_.omask, sc_.slot_of, d_counts);
     SC_LAUNCH(KID_STRIDED_FLAGS, k_strided_flags, dim3((unsigned)nblk), dim3(1024), 0, s, n,
               (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, sc_.flagword, sc_.word_prefix, sc_.block_sum);
-    SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum,
-              sc_.block_prefix, nblk, d_counts);
-    SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
-              (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
-              (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, nbr, (int4*)d_out_coords,
-              (KmapHeader*)d_kmap, h);
+    if (nblk <= SCAN_IN_PAIRS_MAX) {
+        SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs<1>, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
+                  (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
+                  (const int32_t*)sc_.word_prefix, (const int32_t*)nullptr, (const int32_t*)sc_.block_sum, (int)nblk, nbr,
+                  (int4*)d_out_coords, d_counts, (KmapHeader*)d_kmap, h);
+    } else {
+        SC_LAUNCH(KID_SCAN_BLOCKS, k_scan_blocks, dim3(1), dim3(1024), 0, s, (const int32_t*)sc_.block_sum,
+                  sc_.block_prefix, nblk, d_counts);
+        SC_LAUNCH(KID_STRIDED_PAIRS, k_strided_pairs<0>, dim3(gb), dim3(256), 0, s, (const int4*)d_coords, n, stride, L.K3,
+                  (const int32_t*)sc_.slot_of, (const uint4*)sc_.oslots, (const uint64_t*)sc_.flagword,
+                  (const int32_t*)sc_.word_prefix, (const int32_t*)sc_.block_prefix, (const int32_t*)sc_.block_sum,
+                  (int)nblk, nbr, (int4*)d_out_coords, d_counts, (KmapHeader*)d_kmap, h);
+    }
     SC_LAUNCH(KID_KMAP_FROM_OFT, k_masks_from_table, dim3((unsigned)L.tiles), dim3(256), 0, s,
               (const int32_t*)nbr, L.K3, L.mw, L.tiles, gmask, (const sc_counts*)d_counts, 0);
     return SC_OK;

@@ -119,3 +119,36 @@ def test_host_side_argument_errors(lib):
     assert lib.sc_conv_up_fwd(17, 10, 32, 48, 64, 1 << 20, 80, 2, 32, 32, F16, F16, None) == binding.SC_EINVAL   # misaligned
     assert binding.strerror(binding.SC_EDUP) == "duplicate input coordinate"
     assert binding.strerror(12345) == "unknown status"
+
+
+def _insert_probe_lengths(lib, coords, n):
+    """Simulate the table build on the host with the library's own probe sequence: number of
+    attempts every key needs until it finds a free slot."""
+    taken = set()
+    lengths = []
+    for b, x, y, z in coords:
+        t = 0
+        while True:
+            slot = lib.sc_hash_probe_slot(int(b), int(x), int(y), int(z), t, n)
+            assert slot >= 0
+            if slot not in taken:
+                taken.add(slot)
+                break
+            t += 1
+        lengths.append(t + 1)
+    return lengths
+
+
+def test_probe_sequence_on_lattice_aligned_keys(lib):
+    """Voxel sets whose coordinates are all multiples of 2 or 4 (down-sampled sets kept at the
+    original scale) must not pile up on a few places of every 64-slot region."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    n = 20000
+    cells = rng.choice(48 ** 3, size=n, replace=False)
+    for lattice in (1, 2, 4):
+        coords = [(0, (c // 2304) * lattice, ((c // 48) % 48) * lattice, (c % 48) * lattice) for c in cells.tolist()]
+        lengths = _insert_probe_lengths(lib, coords, n)
+        assert sum(lengths) / n < 1.1, (lattice, sum(lengths) / n)
+        assert max(lengths) <= 6, (lattice, max(lengths))
+    assert lib.sc_hash_probe_slot(0, -1, 0, 0, 0, n) == -1

@@ -263,6 +263,27 @@ def test_hash_rebuild_errors_surface_at_the_map_build():
     assert sc.sc_counts_read(counts, check=False).status == sc.SC_ECAP
 
 
+def test_hash_rebuild_error_with_epochs_out_of_order():
+    """Epochs may be used in any order between two sc_hash_build calls: an error left under a
+    higher epoch must not hide the error of a later build with a lower one."""
+    say("hash rebuild errors, epochs 5 then 3")
+    n = 500
+    coords = synth.uniform_cells(n, 16, seed=1)
+    dup = coords.copy()
+    dup[400] = dup[17]
+    bad = coords.copy()
+    bad[7, 3] = -4
+    table, counts = fresh_table(n)
+    kmap = torch.empty(sc.sc_kmap_bytes(n, 3, 1, "subm"), dtype=torch.uint8, device=DEV)
+    sc.sc_hash_build(torch.from_numpy(coords).to(DEV), table, counts)
+    for epoch, wrong, code in ((5, dup, sc.SC_EDUP), (3, dup, sc.SC_EDUP), (4, bad, sc.SC_ERANGE), (2, coords, 0),
+                               (1, dup, sc.SC_EDUP)):
+        d = torch.from_numpy(wrong).to(DEV)
+        sc.sc_hash_rebuild(d, table, epoch, counts)
+        sc.sc_kmap_build(d, table, 3, 1, "subm", None, kmap, None, counts)
+        assert sc.sc_counts_read(counts, check=False).status == code, (epoch, code)
+
+
 def test_hash_rebuild_of_a_large_table():
     """Above 64 MiB of table a rebuild fills the table after all (and then reports its errors
     like sc_hash_build): same results as for small tables, whichever way the library takes."""
@@ -422,6 +443,21 @@ def test_strided_small(K, s, n):
     check_layer(coords, K, s, "strided", 8, 24, "f32", seed=n)
 
 
+def test_strided_map_of_a_set_too_large_for_the_in_kernel_scan():
+    """More than 4096 blocks of 1024 inputs: the block counts are then scanned by a kernel of
+    their own (below that, every workgroup of the pairs kernel scans them itself)."""
+    say("strided map, 4.3 M inputs")
+    n = 4_300_000
+    coords = synth.uniform_cells(n, 180, seed=11)
+    buf = sc.LayerBuffers(n, 2, 2, "strided", 32, 32, "f16", device=DEV)
+    d = torch.from_numpy(coords).to(DEV)
+    buf.kmap_build(d, standalone=True)
+    h = buf.read_counts()
+    ref_km = oracle.kmap(coords, 2, 2, "strided")
+    assert h.status == 0 and h.n_out == ref_km["n_out"] and h.n_pairs == n
+    assert_maps_equal(exported_map(buf, h), buf.out_coords[:h.n_out].cpu().numpy(), ref_km, exact_order=True)
+
+
 @pytest.mark.parametrize("K,s", [(3, 2), (3, 1), (4, 2), (5, 2), (5, 3), (2, 1), (5, 5), (7, 7)])
 @pytest.mark.parametrize("n", [1, 65, 900])
 def test_strided_general_kernel_and_stride(K, s, n):
@@ -522,22 +558,26 @@ def test_strided_build_without_a_table_is_self_contained():
             assert_maps_equal(exported_map(buf, h), buf.out_coords[:h.n_out].cpu().numpy(), ref_km, exact_order=True)
 
 
-def test_maps_are_reproducible_bit_for_bit():
-    """The same input gives the same kernel-map bytes and the same output coordinates on every
-    run (no dependence on thread timing)."""
+def test_maps_and_outputs_are_reproducible_bit_for_bit():
+    """The same input gives the same kernel-map bytes, the same output coordinates and the same
+    output features on every run, 20 runs of every call (no dependence on thread timing)."""
     say("determinism")
     coords = synth.lidar_scene(1)[:30000]
     d = torch.from_numpy(coords).to(DEV)
-    for mode, K, s in (("subm", 3, 1), ("strided", 2, 2)):
-        buf = sc.LayerBuffers(len(coords), K, s, mode, 32, 32, "f16", device=DEV)
+    n = len(coords)
+    for mode, K, s, C_in, C_out in (("subm", 3, 1, 32, 32), ("strided", 2, 2, 32, 64), ("strided", 3, 2, 32, 32),
+                                    ("subm", 3, 1, 64, 64)):
+        d_feat = to_dev(synth.features(n, C_in, "f16", 3), "f16")
+        d_w = to_dev(synth.weights(K ** 3, C_in, C_out, "f16", 3), "f16")
+        buf = sc.LayerBuffers(n, K, s, mode, C_in, C_out, "f16", device=DEV)
         ref = None
-        for _ in range(5):
+        for _ in range(20):
             buf.kmap.zero_()
-            buf.hash_build(d)
-            buf.kmap_build(d)
+            buf.feat_out.zero_()
+            buf.layer(d, d_feat, d_w)
             h = buf.read_counts()
             pin, pout, ost = buf.export(h)
-            cur = (pin.clone(), pout.clone(), ost.clone(), buf.out_coords[:h.n_out].clone())
+            cur = (pin.clone(), pout.clone(), ost.clone(), buf.out_coords[:h.n_out].clone(), buf.feat_out[:h.n_out].clone())
             if ref is None:
                 ref = cur
             else:
@@ -554,6 +594,43 @@ def test_delta_weight_passthrough():
         W[13] = np.eye(C)
         _, _, _, out = run_layer(coords, feat, W, 3, 1, "subm", dtype)
         assert np.array_equal(out, feat.astype(np.float64))
+
+
+SHIFT_SHAPES = [("f32", 16, 16, 1500), ("f16", 32, 32, 1500), ("f16", 32, 32, 40000), ("f16", 64, 64, 1500),
+                ("bf16", 128, 128, 1500), ("f16", 32, 64, 1500), ("bf16", 64, 128, 1500), ("f16", 256, 32, 600)]
+
+
+@pytest.mark.parametrize("dtype,C_in,C_out,n", SHIFT_SHAPES)
+def test_shifted_delta_weights(dtype, C_in, C_out, n):
+    """W[k0] = (I | 0) for one offset k0 other than the centre: output row i must equal, bit for
+    bit, the first C_out (or all C_in) channels of the input row of the voxel at p_i + d_k0 - pad,
+    or zero where there is none.  Pins the per-offset indexing of every dedicated kernel (the 40,000
+    row case takes the four-tiles-per-workgroup form of the 32 -> 32 kernel)."""
+    say(f"shifted delta {dtype} {C_in}->{C_out} n={n}")
+    grid = 12 if n <= 1500 else 40
+    coords = synth.uniform_cells(n, grid, seed=n + C_in)
+    feat = synth.features(n, C_in, dtype, 6)
+    lookup = {tuple(r): i for i, r in enumerate(coords.tolist())}
+    cc = min(C_in, C_out)
+    for k0 in (0, 5, 24, 26):
+        W = np.zeros((27, C_in, C_out), np.float32)
+        W[k0, :cc, :cc] = np.eye(cc)
+        _, _, _, out = run_layer(coords, feat, W, 3, 1, "subm", dtype)
+        d = (k0 // 9 - 1, (k0 // 3) % 3 - 1, k0 % 3 - 1)
+        src = np.array([lookup.get((b, x + d[0], y + d[1], z + d[2]), -1) for b, x, y, z in coords.tolist()])
+        want = np.zeros((n, C_out))
+        hit = src >= 0
+        want[hit, :cc] = feat[src[hit], :cc]
+        assert np.array_equal(out, want), k0
+
+
+def test_resident_kernel_with_four_tiles_per_workgroup_fp32_output():
+    """32 -> 32 channels on >= 512 tiles takes the NT = 4 form of the resident kernel: held to
+    the oracle with fp32 output (only the order of summation differs: 1e-5)."""
+    say("32->32, 512+ tiles, fp32 output")
+    coords = synth.lidar_scene(4)[:40000]
+    err = check_layer(coords, 3, 1, "subm", 32, 32, "f16", seed=4, out_dtype="f32", threads=16)
+    assert err <= 1e-5
 
 
 # ---- map reuse and the inverse layer ------------------------------------------------------------
@@ -824,7 +901,12 @@ def test_cfg5_full_map_and_sampled_outputs():
     assert h.n_pairs == ref_km["offset_start"][-1]
     assert_maps_equal(exported_map(buf, h), out_coords, ref_km, exact_order=True)
     rng = np.random.default_rng(0)
-    rows = np.unique(np.concatenate([rng.choice(n, 20000, replace=False), np.arange(0, 200), np.arange(n - 200, n)]))
+    # a random sample, both ends, and whole 64-row tiles on either side of every boundary between
+    # the eighths the convolution hands to the 8 XCDs (8 tiles per workgroup: the unit is 512 rows)
+    units = (n + 511) // 512
+    chunk = (units + 7) // 8
+    edges = [np.arange(max(0, c * chunk * 512 - 128), min(n, c * chunk * 512 + 128)) for c in range(1, 8)]
+    rows = np.unique(np.concatenate([rng.choice(n, 20000, replace=False), np.arange(0, 200), np.arange(n - 200, n)] + edges))
     keep = np.isin(ref_km["pair_out"], rows)
     ost = np.zeros(28, np.int64)
     for k in range(27):
