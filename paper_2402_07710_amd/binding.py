@@ -380,6 +380,10 @@ class LayerBuffers:
                 self.epoch = 1
             sc_grid_build(coords, self.table, self.grid_dims, self.epoch, self.counts, stream)
 
+    def forget_table(self):
+        """Make the next hash_build a full sc_hash_build (fill + inserts), as on a fresh table."""
+        self._hash_n = None
+
     def kmap_build(self, coords, stream=None, standalone=False):
         """standalone (strided layers): no location table is passed, the build starts the counts
         block itself and repeated input coordinates go unnoticed."""
