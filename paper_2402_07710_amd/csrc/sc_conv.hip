@@ -270,17 +270,15 @@ __device__ __align__(256) uint4 g_zero_row[32];      // 512 bytes: a row of up t
 //    multiplies are skipped, so all waits are exact counts.
 // Accumulators (64 rows x C_out per wavefront) never leave the registers.  KS = C_in/32,
 // CB = C_out/16.
-// RC = 1 gathers rows lane-contiguously.  The texture path serves a 64-lane load four consecutive
-// lanes per cycle when they read one 64-byte segment and one lane per cycle when they do not
-// (measured: 65 cycles per instruction in the operand's lane order, where consecutive lanes
-// belong to different rows; 18 with four consecutive lanes on the four 16-byte pieces of one
-// row).  The rows then arrive in "load layout" and pass through a small per-wavefront LDS area
-// (swizzled slots) right before use to come back in operand layout.  It pays where the gather
-// dominates (64 channels: -9 % on ~10^5 voxels); for 128 channels the extra LDS traffic costs
-// more than the gather saves, and an in-register shuffle (lane-swap + quad-permute
-// instructions, 20 VALU operations per 16 bytes) was measured slower than either.
+// Rows are gathered in the operand's own lane order (16 rows x four 16-byte pieces of a 32-channel
+// slice per load: 64 contiguous bytes of a row).  Gathering whole 128-byte rows with eight
+// consecutive lanes per row is cheaper for the address unit, but the rows then have to pass
+// through LDS to reach operand layout; k_conv_direct64 does that for 64 input channels, where a
+// row is one line.  For wider rows the extra LDS traffic costs more than the gather saves, and an
+// in-register shuffle (lane-swap + quad-permute instructions, 20 VALU operations per 16 bytes)
+// was measured slower than either.
 // FUSED: as in k_conv_rows16, the offset-table lines come from the dense location table directly.
-template <int DT, int K3, int KS, int CB, int NWV, int D, int RC, int FUSED>
+template <int DT, int K3, int KS, int CB, int NWV, int D, int FUSED>
 __global__ void __launch_bounds__(64 * NWV, 2)
 k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
               const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
@@ -295,15 +293,12 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
     constexpr int WPT = WK / NTH;                     // uint4 per thread per W[k]
     constexpr int CBG = CB < 4 ? CB : 4;              // weight operands held at a time
     static_assert(CB % CBG == 0, "whole operand batches");
-    constexpr int RB = C_in * 2;                      // bytes per feature row
-    extern __shared__ __align__(16) uint4 smem[];     // w_lds[2][WK] | stage[NWV][16 rows] | e_lds[NWV][K3][64]
+    extern __shared__ __align__(16) uint4 smem[];     // w_lds[2][WK] | e_lds[NWV][K3][64]
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int r = lane & 15, qq = lane >> 4;
     uint4* w_lds = smem;
-    constexpr int STAGE = RC ? 4 * 16 * RB : 0;      // bytes of the per-wavefront staging area (one part per group)
-    char* stage = reinterpret_cast<char*>(smem + 2 * WK) + wv * STAGE;
-    int32_t* e_lds = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(smem + 2 * WK) + NWV * STAGE) + wv * (K3 * TILE);
+    int32_t* e_lds = reinterpret_cast<int32_t*>(smem + 2 * WK) + wv * (K3 * TILE);
     SC_MARK(0);
     int64_t n_out = n_out_cap;
     if (!FUSED && *n_out_ptr < n_out) n_out = *n_out_ptr;
@@ -355,27 +350,16 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
 #pragma unroll
         for (int i = 0; i < WPT; ++i) wr[j][i] = wsrc[(int64_t)j * WK + i * NTH];
 
-    // which row of a group and which 16-byte piece of a 32-channel slice this lane gathers: the
-    // operand's own lane order, or (RC) four consecutive lanes on the four pieces of one row
-    const int lrow = RC ? lane >> 2 : r, lpiece = RC ? lane & 3 : qq;
-    // staging area of one group: [16 rows][RB bytes], the 16-byte slots of a row swizzled with the
-    // row number so that both the row-wise stores and the column-wise operand reads spread over the banks
-    auto swz = [](int row) -> int { return KS == 1 ? ((row >> 1) & 3) : (row & 7); };
-    int st_w[KS], st_r[KS];
-#pragma unroll
-    for (int i = 0; i < KS; ++i) {
-        st_w[i] = lrow * RB + (((i * 4 + lpiece) ^ swz(lrow)) << 4);
-        st_r[i] = r * RB + (((i * 4 + qq) ^ swz(r)) << 4);
-    }
+    // a lane gathers row lane % 16 of a group, the (lane / 16)-th 16-byte piece of a 32-channel slice
     auto rowptr = [&](int32_t e) -> const uint4* {
-        return (e >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e * C_in) : g_zero_row) + lpiece;
+        return (e >= 0 ? reinterpret_cast<const uint4*>(feat + (int64_t)e * C_in) : g_zero_row) + qq;
     };
     uint4 fb[D][4][KS];
 #pragma unroll
     for (int j = 0; j < D && j < K3; ++j) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const uint4* frow = rowptr(e_lds[j * TILE + g * 16 + lrow]);
+            const uint4* frow = rowptr(e_lds[j * TILE + g * 16 + r]);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) fb[j][g][ks] = frow[ks * 4];
         }
@@ -400,26 +384,9 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
         int32_t e4[4] = {-1, -1, -1, -1};
         if (more) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) e4[g] = e_lds[(k + D) * TILE + g * 16 + lrow];
+            for (int g = 0; g < 4; ++g) e4[g] = e_lds[(k + D) * TILE + g * 16 + r];
         }
         __builtin_amdgcn_sched_barrier(0);            // the fetches are issued here, not next to their use
-        // the rows of this offset: load layout -> operand layout through the staging area (all stores,
-        // then all loads: one LDS round trip per step; a wavefront's LDS operations execute in order,
-        // so the area can be reused at the next step without further ado)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            if (RC && ((mg[g] >> k) & 1u)) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) *reinterpret_cast<uint4*>(stage + g * (16 * RB) + st_w[ks]) = fb[k % D][g][ks];
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            if (RC && ((mg[g] >> k) & 1u)) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) fb[k % D][g][ks] = *reinterpret_cast<const uint4*>(stage + g * (16 * RB) + st_r[ks]);
-            }
-        }
         const uint4* wk = w_lds + (k & 1) * WK + lane;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -467,6 +434,323 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
             if (row < n_out) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) store_acc<DT>(out, out_f32, row, C_out, cb * 16 + qq * 4, acc[g][cb]);
+            }
+        }
+    }
+    SC_MARK(4);
+    SC_MARK(5);
+}
+
+// ---- 64 input channels: independent wavefronts, weights straight from global memory ---------------
+// One wavefront per 64-row tile as in k_conv_stream, but nothing is shared between the wavefronts
+// of a workgroup: no weight tile in LDS, no barrier.  A layer of ~10^5 voxels keeps every CU busy
+// with a handful of wavefronts, each of which walks its K^3 offsets as one chain; what a step of
+// that chain costs is the latency of what it has to wait for, so everything a step needs is
+// requested one to two steps ahead and a wavefront never waits for another one.
+//  * Multiplies are v_mfma_f32_32x32x16 on the two 32-row halves of the tile; a half without a
+//    neighbour at offset k is skipped, and so are its loads.
+//  * The weight operand of that instruction (32 output channels x 16 input channels) is read
+//    straight from the packed 16x32 tiles in global memory, one step ahead: both forms keep 8
+//    input channels of one output channel in 16 bytes, so only the addresses differ, and a load
+//    touches eight whole 128-byte lines.  Every wavefront of the chip reads the same 8 KB per
+//    offset: L1 and L2 hits.
+//  * Gathers are buffer loads, eight lanes on the eight 16-byte pieces of one 128-byte row: the
+//    address is one shift-or (row << 7 | byte in row), and "no neighbour" (row -1) lands beyond
+//    the buffer's range, where the hardware returns zeros without touching memory.  The rows
+//    land in a ring of three register slots and pass through a 4 KB staging area in LDS (swizzled
+//    16-byte slots) to come back in operand layout, one step before they are multiplied.
+//  * Loads inside the loop are inline assembly, so that the compiler places no waits of its own
+//    for them: which loads are issued depends on the tile, and the one wait per step names the
+//    exact number of younger loads that may stay in flight (the counter retires in order).
+//    Registers written by such a load are handed back to the compiler through an empty asm
+//    statement right after the wait that covers them.
+//  * In program order the staging operations of offset k+1 sit between the multiplies of offset
+//    k: a wavefront's LDS operations then run in the shadow of its own matrix instructions.
+// The feature array must be smaller than 4 GiB (32-bit buffer offsets); the host checks and falls
+// back to k_conv_stream otherwise.  The number of tiles per workgroup is the launch's block size
+// / 64 (any value up to 8): the host picks it so that the workgroups spread evenly over the CUs.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+template <int DT>
+__device__ inline f32x16 mfma32x32x16(u32x4 a, u32x4 b, f32x16 c) {
+    if constexpr (DT == SC_F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+template <int N> struct IntC { static constexpr int value = N; };
+constexpr int DIRECT_STEPS(int K3) { return (K3 + 5) / 6 * 6; }      // six steps per trip of the loop
+constexpr int DIRECT_LINES(int K3) { return DIRECT_STEPS(K3) + 3; }  // table lines kept in LDS per wavefront
+constexpr int DIRECT_STAGE = 32 * 128;                               // bytes of a wavefront's staging area
+
+template <int DT, int K3, int FUSED>
+__global__ void __launch_bounds__(512, 1)
+k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
+                const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
+    static_assert(K3 <= 60, "one 64-bit mask word per half, bits of the look-ahead included");
+    static_assert(!FUSED || K3 == 27, "fused look-ups: 3x3x3 layers");
+    const uint32_t* __restrict__ gmask = ms.gmask;
+    const int32_t* __restrict__ nbr = ms.nbr;
+    constexpr int MB = 2, C_out = 64, RB = 128;       // 32-channel output blocks, bytes per feature row
+    constexpr int KP = DIRECT_STEPS(K3);               // steps; the ones at or above K3 do nothing
+    constexpr int KE = DIRECT_LINES(K3);               // real lines, then lines of "no neighbour"
+    extern __shared__ __align__(16) uint4 smem[];     // stage[NWV][32 rows x 128 B] | e_lds[NWV][KE][64]
+
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, NWV = blockDim.x >> 6;
+    const int r32 = lane & 31, hh = lane >> 5;
+    char* stage = reinterpret_cast<char*>(smem) + wv * DIRECT_STAGE;
+    int32_t* e_lds = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(smem) + NWV * DIRECT_STAGE) + wv * (KE * TILE);
+    int64_t n_out = n_out_cap;
+    if (!FUSED && *n_out_ptr < n_out) n_out = *n_out_ptr;
+    // a workgroup's tiles are spread over the whole row range (tile = wavefront * units + unit):
+    // neighbouring tiles are alike in how many offsets they take part in, and the kernel ends with
+    // its slowest workgroup
+    const int64_t units = (n_out + (int64_t)NWV * TILE - 1) / ((int64_t)NWV * TILE);
+    const int64_t unit = xcd_unit_of(blockIdx.x, units);
+    if (unit < 0) return;
+    SC_MARK(0);
+    const int64_t tile = wv * units + unit;
+    const bool tile_ok = tile * TILE < n_out;
+
+    uint64_t mg[2] = {0ull, 0ull};                     // which offsets each 32-row half takes part in (bits < K3)
+    if constexpr (FUSED) {
+        int32_t v[K3];
+        if (tile_ok) {
+            grid_neighbours<3>(ms, tile * TILE + lane, n_out, v);
+#pragma unroll
+            for (int k = 0; k < K3; ++k) {
+                const uint64_t vote = __ballot(v[k] >= 0);
+#pragma unroll
+                for (int g = 0; g < 2; ++g) mg[g] |= (uint64_t)(((vote >> (32 * g)) & 0xffffffffull) != 0ull ? 1u : 0u) << k;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < K3; ++k) v[k] = -1;
+        }
+#pragma unroll
+        for (int k = 0; k < K3; ++k) e_lds[k * TILE + lane] = v[k];
+    } else {
+        // the tile's K3 table lines are one contiguous piece of the map: 16 bytes per lane and load
+        constexpr int LINE16 = K3 * TILE / 4;          // 16-byte pieces
+        constexpr int PASSES = (LINE16 + 63) / 64;
+        u32x4 v[PASSES];
+        const u32x4* line = reinterpret_cast<const u32x4*>(nbr + tile * (int64_t)(K3 * TILE));
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i)
+            v[i] = (tile_ok && i * 64 + lane < LINE16) ? line[i * 64 + lane] : u32x4{~0u, ~0u, ~0u, ~0u};
+        if (tile_ok) {
+#pragma unroll
+            for (int g = 0; g < 2; ++g) mg[g] = gmask[tile * 4 + 2 * g] | gmask[tile * 4 + 2 * g + 1];
+        }
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i)
+            if (i * 64 + lane < LINE16) reinterpret_cast<u32x4*>(e_lds)[i * 64 + lane] = v[i];
+    }
+#pragma unroll
+    for (int k = K3; k < KE; ++k) e_lds[k * TILE + lane] = -1;
+#pragma unroll
+    for (int g = 0; g < 2; ++g) mg[g] = (uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)mg[g]);
+    auto pattern_at = [&](int k) -> uint32_t { return (uint32_t)((mg[0] >> k) & 1u) | ((uint32_t)((mg[1] >> k) & 1u) << 1); };
+    auto halves_at = [&](int k) -> uint32_t { return (uint32_t)((mg[0] >> k) & 1u) + (uint32_t)((mg[1] >> k) & 1u); };
+
+    // gathers: instruction i of a half reads its rows 8i .. 8i+7, eight lanes per row
+    const int row8 = lane >> 3, piece = lane & 7;
+    // buffer descriptor over the feature array: offsets at or above 0xFFFFFF80 (row -1) read as zeros
+    u32x4 rs;
+    {
+        const uint64_t fa = (uint64_t)feat;
+        rs[0] = __builtin_amdgcn_readfirstlane((uint32_t)fa);
+        rs[1] = __builtin_amdgcn_readfirstlane((uint32_t)(fa >> 32) & 0xffffu);
+        rs[2] = __builtin_amdgcn_readfirstlane(0xFFFFFF80u);
+        rs[3] = __builtin_amdgcn_readfirstlane(0x00020000u);
+    }
+    const uint32_t pbyte = piece << 4;
+    // staging area: [32 rows][128 bytes], the 16-byte slots of a row swizzled with the row number;
+    // the multiply's operand for 16-channel slice s is piece 2s + (lane / 32) of row lane % 32
+    int st_w[4], st_r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        st_w[i] = (8 * i + row8) * RB + ((piece ^ row8) << 4);
+        st_r[i] = r32 * RB + (((2 * i + hh) ^ (r32 & 7)) << 4);
+    }
+    const int32_t* e_mine = e_lds + row8;
+    auto row_offsets = [&](uint32_t (&off)[2][4], int k) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) off[g][i] = ((uint32_t)e_mine[k * TILE + g * 32 + i * 8] << 7) | pbyte;
+    };
+    // the rows of one offset for the halves named by pat: four loads per half, skipped as a whole otherwise
+    auto gather = [&](u32x4 (&dst)[2][4], const uint32_t (&off)[2][4], uint32_t pat) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+            asm volatile(
+                "s_bitcmp1_b32 %[pat], %[bit]\n\t"
+                "s_cbranch_scc0 .Lsc_skip_%=\n\t"
+                "buffer_load_dwordx4 %[d0], %[o0], %[rs], 0 offen\n\t"
+                "buffer_load_dwordx4 %[d1], %[o1], %[rs], 0 offen\n\t"
+                "buffer_load_dwordx4 %[d2], %[o2], %[rs], 0 offen\n\t"
+                "buffer_load_dwordx4 %[d3], %[o3], %[rs], 0 offen\n"
+                ".Lsc_skip_%=:"
+                : [d0] "+v"(dst[g][0]), [d1] "+v"(dst[g][1]), [d2] "+v"(dst[g][2]), [d3] "+v"(dst[g][3])
+                : [o0] "v"(off[g][0]), [o1] "v"(off[g][1]), [o2] "v"(off[g][2]), [o3] "v"(off[g][3]), [rs] "s"(rs),
+                  [pat] "s"(pat), [bit] "n"(g)
+                : "scc");
+    };
+    // the eight weight operands of offset k (slice sl, output block mb), skipped if the tile takes no part
+    const int a_lane = 2048 * ((lane >> 4) & 1) + 256 * hh + 16 * (lane & 15);
+    const char* w_lane = reinterpret_cast<const char*>(wp) + a_lane;
+    auto load_weights = [&](u32x4 (&dst)[4][MB], int k, uint32_t pat) {
+        const char* p0 = w_lane + (int64_t)(k < K3 ? k : K3 - 1) * (4 * MB * 1024);
+        const char* p1 = p0 + 4096;
+        asm volatile(
+            "s_cmp_eq_u32 %[pat], 0\n\t"
+            "s_cbranch_scc1 .Lsc_skipw_%=\n\t"
+            "global_load_dwordx4 %[d0], %[p0], off\n\t"
+            "global_load_dwordx4 %[d1], %[p1], off\n\t"
+            "global_load_dwordx4 %[d2], %[p0], off offset:512\n\t"
+            "global_load_dwordx4 %[d3], %[p1], off offset:512\n\t"
+            "global_load_dwordx4 %[d4], %[p0], off offset:1024\n\t"
+            "global_load_dwordx4 %[d5], %[p1], off offset:1024\n\t"
+            "global_load_dwordx4 %[d6], %[p0], off offset:1536\n\t"
+            "global_load_dwordx4 %[d7], %[p1], off offset:1536\n"
+            ".Lsc_skipw_%=:"
+            : [d0] "+v"(dst[0][0]), [d1] "+v"(dst[0][1]), [d2] "+v"(dst[1][0]), [d3] "+v"(dst[1][1]),
+              [d4] "+v"(dst[2][0]), [d5] "+v"(dst[2][1]), [d6] "+v"(dst[3][0]), [d7] "+v"(dst[3][1])
+            : [p0] "v"(p0), [p1] "v"(p1), [pat] "s"(pat)
+            : "scc");
+    };
+    // wait until at most 4 n loads are outstanding (n: halves fetched by the step before)
+    auto wait_younger = [&](uint32_t n) {
+        if (n == 0u) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (n == 1u) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    };
+    // hand the registers of finished loads back to the compiler
+    auto pin = [&](u32x4 (&slot)[2][4]) {
+        asm volatile("" : "+v"(slot[0][0]), "+v"(slot[0][1]), "+v"(slot[0][2]), "+v"(slot[0][3]),
+                          "+v"(slot[1][0]), "+v"(slot[1][1]), "+v"(slot[1][2]), "+v"(slot[1][3]));
+    };
+    auto pin_w = [&](u32x4 (&w)[4][MB]) {
+        asm volatile("" : "+v"(w[0][0]), "+v"(w[0][1]), "+v"(w[1][0]), "+v"(w[1][1]),
+                          "+v"(w[2][0]), "+v"(w[2][1]), "+v"(w[3][0]), "+v"(w[3][1]));
+    };
+    u32x4 fb[3][2][4], a[2][4][MB];
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fb[j][g][i] = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) a[j][sl][mb] = u32x4{0u, 0u, 0u, 0u};
+    // before the loop: the weights of offset 0 and the rows of offsets 0..2, all complete at its start
+    load_weights(a[0], 0, pattern_at(0));
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        uint32_t off[2][4];
+        row_offsets(off, j);
+        gather(fb[j], off, pattern_at(j));
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < 3; ++j) pin(fb[j]);
+    pin_w(a[0]);
+    f32x16 acc[2][MB];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[g][mb][j] = 0.f;
+    // rows of offset 0: load layout -> operand layout through the staging area (one half after the
+    // other through the same 4 KB: a wavefront's LDS operations execute in order)
+    {
+        const uint32_t pat0 = pattern_at(0);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            if ((pat0 >> g) & 1u) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(stage + st_w[i]) = fb[0][g][i];
+#pragma unroll
+                for (int sl = 0; sl < 4; ++sl) fb[0][g][sl] = *reinterpret_cast<const u32x4*>(stage + st_r[sl]);
+            }
+        }
+    }
+    SC_MARK(1);
+    SC_MARK(2);
+
+    // One step.  At its start the rows of offset k are in ring slot S in operand layout and its
+    // weights are in a[AB] (possibly still on their way: the wait comes first); the rows of offset
+    // k+1 are in slot S1 in load layout, those of k+2 in flight.  Loads in issue order:
+    // ... weights k, rows k+2 | weights k+1, rows k+3: what may stay in flight at the top of step k
+    // are the rows of k+2, four loads per half that takes part.  Then the weights of offset k+1 are
+    // requested, the multiplies of offset k are issued slice by slice with the staging of offset
+    // k+1 between them (half 0 is written in slice 0 and read back in slice 1, half 1 in slices 2
+    // and 3), and the freed slot is refilled with the rows of offset k+3.
+    auto step = [&](auto slot_c, auto ab_c, int k) {
+        constexpr int S = decltype(slot_c)::value, S1 = (S + 1) % 3, AB = decltype(ab_c)::value;
+        const uint32_t pat = pattern_at(k), pat1 = pattern_at(k + 1), pat3 = pattern_at(k + 3);
+        wait_younger(halves_at(k + 2));
+        pin(fb[S1]);
+        pin_w(a[AB]);
+        load_weights(a[1 - AB], k + 1, pat1);
+        uint32_t off[2][4];
+        row_offsets(off, k + 3);       // read now, used after the multiplies have been issued
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                if ((pat >> g) & 1u) {
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) acc[g][mb] = mfma32x32x16<DT>(a[AB][sl][mb], fb[S][g][sl], acc[g][mb]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (g == 0) {
+                    const int h = sl >> 1;          // the half whose staging falls into this slice
+                    if ((pat1 >> h) & 1u) {
+                        if ((sl & 1) == 0) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(stage + st_w[i]) = fb[S1][h][i];
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) fb[S1][h][i] = *reinterpret_cast<const u32x4*>(stage + st_r[i]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        gather(fb[S], off, pat3);
+    };
+    // six steps per trip, so that ring slots (three) and weight registers (two sets) are constants
+#pragma unroll 1
+    for (int k = 0; k < KP; k += 6) {
+        step(IntC<0>{}, IntC<0>{}, k);
+        step(IntC<1>{}, IntC<1>{}, k + 1);
+        step(IntC<2>{}, IntC<0>{}, k + 2);
+        step(IntC<0>{}, IntC<1>{}, k + 3);
+        step(IntC<1>{}, IntC<0>{}, k + 4);
+        step(IntC<2>{}, IntC<1>{}, k + 5);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing of the loop's loads is left in flight
+    SC_MARK(3);
+    // the accumulator block of a lane: output row lane % 32 of the half, channels
+    // 32 mb + 8 q + 4 (lane / 32) .. + 3 for q = 0..3
+    if (tile_ok) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            const int64_t row = tile * TILE + g * 32 + r32;
+            if (row < n_out) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        store_acc<DT>(out, out_f32, row, C_out, mb * 32 + 8 * q + 4 * hh,
+                                      f32x4{acc[g][mb][4 * q], acc[g][mb][4 * q + 1], acc[g][mb][4 * q + 2], acc[g][mb][4 * q + 3]});
             }
         }
     }
@@ -708,15 +992,48 @@ static int launch_resident(int K3, int C_in, int C_out, int64_t tiles, hipStream
     return SC_OK;
 }
 
-template <int DT, int K3, int KS, int CB, int NWV, int D, int RC, int FUSED>
+template <int DT, int K3, int KS, int CB, int NWV, int D, int FUSED>
 static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                          const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, RC, FUSED>;
-    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) + (RC ? (size_t)NWV * 4 * 16 * KS * 64 : 0) +
+    auto fn = k_conv_stream<DT, K3, KS, CB, NWV, D, FUSED>;
+    const size_t lds = (size_t)2 * CB * KS * 64 * sizeof(uint4) +
                        (size_t)NWV * K3 * TILE * sizeof(int32_t);
     static bool allowed[MAX_DEVICES] = {};
     if (int rc = allow_lds((const void*)fn, lds, allowed)) return rc;
     SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + NWV - 1) / NWV)), dim3(64 * NWV), lds, s, feat, wp, out, out_f32,
+              ms, counts, n_out_cap);
+    return SC_OK;
+}
+
+// Tiles per workgroup for k_conv_direct64: its wavefronts are independent, so any count up to 8
+// (two wavefronts per SIMD at its register use) works; the workgroups should land on the CUs evenly.
+// Up to 8 tiles per CU: one workgroup per CU with ceil(tiles / CUs) wavefronts (measured on ~110 k
+// voxels: 31.4 us with 7, 33.3 with 8, 35.1 with 4); beyond that, four (261 k voxels: 62.6 us
+// with 4, 64.0 with 8, 78.1 with 7).
+static int direct_tiles_per_workgroup(int64_t tiles) {
+    static int cu_count[MAX_DEVICES] = {};      // per device, asked once (a race between host threads stores the same value)
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < MAX_DEVICES) {
+        if (cu_count[dev] == 0) {
+            int n = 0;
+            cu_count[dev] = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0 ? n : 256;
+        }
+        cus = cu_count[dev];
+    }
+    if (tiles > (int64_t)cus * 8) return 4;
+    const int64_t per_cu = (tiles + cus - 1) / cus;
+    return per_cu < 1 ? 1 : (int)per_cu;
+}
+template <int DT, int K3, int FUSED>
+static int launch_direct64(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
+                           const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
+    auto fn = k_conv_direct64<DT, K3, FUSED>;
+    const size_t lds_max = (size_t)8 * (DIRECT_STAGE + DIRECT_LINES(K3) * TILE * sizeof(int32_t));
+    static bool allowed[MAX_DEVICES] = {};
+    if (int rc = allow_lds((const void*)fn, lds_max, allowed)) return rc;
+    const int nwv = direct_tiles_per_workgroup(tiles);
+    const size_t lds = (size_t)nwv * (DIRECT_STAGE + DIRECT_LINES(K3) * TILE * sizeof(int32_t));
+    SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + nwv - 1) / nwv)), dim3(64 * nwv), lds, s, feat, wp, out, out_f32,
               ms, counts, n_out_cap);
     return SC_OK;
 }
@@ -743,17 +1060,20 @@ static int launch_up(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, 
 template <int DT, int FUSED>
 static int launch_streamed(int K3, int C_in, int C_out, int64_t tiles, hipStream_t s, const uint16_t* feat,
                            const uint4* wp, void* out, int out_f32, const MapSource& ms, const int64_t* counts,
-                           int64_t n_out_cap, bool* handled) {
+                           int64_t n_out_cap, bool feat_small, bool* handled) {
     *handled = true;
-#define SC_STREAM(K3V, KSV, CBV, NWV, DV, RCV) \
-    return launch_stream<DT, K3V, KSV, CBV, NWV, DV, RCV, FUSED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
-    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4, 4, 3, 1);
-    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1, 0);
-    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3, 0);
-    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2, 0);
+    // 64 input channels: the kernel with 32-bit buffer offsets where the feature array allows it
+    if (K3 == 27 && C_in == 64 && C_out == 64 && feat_small)
+        return launch_direct64<DT, 27, FUSED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap);
+#define SC_STREAM(K3V, KSV, CBV, NWV, DV) \
+    return launch_stream<DT, K3V, KSV, CBV, NWV, DV, FUSED>(tiles, s, feat, wp, out, out_f32, ms, counts, n_out_cap)
+    if (K3 == 27 && C_in == 64 && C_out == 64) SC_STREAM(27, 2, 4, 4, 3);       // feature arrays of 4 GiB and more
+    if (K3 == 27 && C_in == 128 && C_out == 128) SC_STREAM(27, 4, 8, 8, 1);
+    if (K3 == 27 && C_in == 32 && C_out == 64) SC_STREAM(27, 1, 4, 4, 3);
+    if (K3 == 27 && C_in == 64 && C_out == 128) SC_STREAM(27, 2, 8, 4, 2);
     if constexpr (!FUSED) {
-        if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2, 0);
-        if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1, 0);
+        if (K3 == 8 && C_in == 64 && C_out == 128) SC_STREAM(8, 2, 8, 4, 2);
+        if (K3 == 8 && C_in == 128 && C_out == 128) SC_STREAM(8, 4, 8, 8, 1);
     }
 #undef SC_STREAM
     *handled = false;
@@ -778,7 +1098,7 @@ static int pack_weights(int K3, int C_in, int C_out, const void* d_weight, void*
 template <int FUSED>
 static int conv_16bit(int dtype_in, int K3, int mw, int C_in, int C_out, int64_t tiles, hipStream_t s, const void* d_feat_in,
                       const void* d_weight, bool packed, void* d_workspace, void* d_feat_out,
-                      int out_f32, const MapSource& ms, const int64_t* n_out_ptr, int64_t n_out_cap) {
+                      int out_f32, const MapSource& ms, const int64_t* n_out_ptr, int64_t n_out_cap, int64_t feat_rows) {
     const uint16_t* feat = (const uint16_t*)d_feat_in;
     bool handled = false;
     int rc;
@@ -804,10 +1124,12 @@ static int conv_16bit(int dtype_in, int K3, int mw, int C_in, int C_out, int64_t
         if (int prc = pack_weights(K3, C_in, C_out, d_weight, d_workspace, s)) return prc;
         wp = (const uint4*)d_workspace;
     }
+    // rows that a 32-bit byte offset can address, with room for the "no neighbour" offsets above them
+    const bool feat_small = feat_rows * (int64_t)C_in * 2 < 0xFFFFFF80ll;
     rc = dtype_in == SC_F16 ? launch_streamed<SC_F16, FUSED>(K3, C_in, C_out, tiles, s, feat, wp, d_feat_out, out_f32, ms,
-                                                            n_out_ptr, n_out_cap, &handled)
+                                                            n_out_ptr, n_out_cap, feat_small, &handled)
                             : launch_streamed<SC_BF16, FUSED>(K3, C_in, C_out, tiles, s, feat, wp, d_feat_out, out_f32, ms,
-                                                             n_out_ptr, n_out_cap, &handled);
+                                                             n_out_ptr, n_out_cap, feat_small, &handled);
     if (handled || rc != SC_OK) return rc;
     if (FUSED) return SC_EINVAL;
     if (dtype_in == SC_F16)
@@ -880,8 +1202,10 @@ static int conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_weight, 
         if (d_workspace == nullptr || workspace_bytes < need) return SC_ECAP;
     }
     const MapSource ms{gmask, nbr, nullptr, nullptr, GridDims{0, 0, 0, 0}, 0u};
+    // rows of the input feature array: the map's inputs, or (inverse layers) at most the strided map's bound
+    const int64_t feat_rows = n_map > bound ? n_map : bound;
     return conv_16bit<0>(dtype_in, L.K3, L.mw, C_in, C_out, tiles, s, d_feat_in, d_weight, packed, d_workspace,
-                         d_feat_out, dtype_out == SC_F32, ms, n_out_ptr, n_out_cap);
+                         d_feat_out, dtype_out == SC_F32, ms, n_out_ptr, n_out_cap, feat_rows);
 }
 
 extern "C" int sc_conv_fwd(const void* d_feat_in, int64_t n_map, const void* d_weight, void* d_feat_out,
@@ -974,5 +1298,5 @@ extern "C" int sc_conv_fwd_grid(const void* d_feat_in, const int32_t* d_coords, 
     const MapSource ms{nullptr, nullptr, (const int4*)d_coords, (const unsigned long long*)d_grid, GridDims{B, X, Y, Z}, epoch};
     if (!mfma_channels_ok(C_in, C_out)) return SC_EINVAL;
     return conv_16bit<1>(dtype_in, 27, 1, C_in, C_out, (n + TILE - 1) / TILE, (hipStream_t)stream, d_feat_in, d_weight,
-                         false, d_workspace, d_feat_out, dtype_out == SC_F32, ms, nullptr, n);
+                         false, d_workspace, d_feat_out, dtype_out == SC_F32, ms, nullptr, n, n);
 }

@@ -782,6 +782,52 @@ def test_random_layers():
 
 
 # ---- the five named configurations at full size ----------------------------------------------
+def sampled_rows_reference(feat, weight, ref_km, rows, threads=16):
+    """The oracle's outputs on `rows` only: the pairs of other output rows are dropped first."""
+    K3 = len(ref_km["offset_start"]) - 1
+    keep = np.isin(ref_km["pair_out"], rows)
+    ost = np.zeros(K3 + 1, np.int64)
+    for k in range(K3):
+        sl = slice(ref_km["offset_start"][k], ref_km["offset_start"][k + 1])
+        ost[k + 1] = ost[k] + int(keep[sl].sum())
+    sub = dict(ref_km, pair_in=ref_km["pair_in"][keep], pair_out=ref_km["pair_out"][keep], offset_start=ost)
+    return oracle.conv(feat, weight, sub, threads=threads)
+
+
+# The 64 -> 64 kernel puts 1..8 tiles into a workgroup depending on how many tiles there are per
+# CU (4 beyond 8 per CU), and spreads a workgroup's tiles over the row range: tile = wavefront *
+# units + unit.  One size per setting on a 256-CU device, fp32 output held to the fp32 tolerance.
+@pytest.mark.parametrize("n_tiles", [255, 300, 600, 1000, 1200, 1500, 1700, 2040, 2300])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_64_channel_layer_at_every_tiles_per_workgroup(n_tiles, dtype):
+    if dtype == "bf16" and n_tiles not in (300, 1700, 2300):
+        pytest.skip("bf16: three sizes")
+    n = n_tiles * 64 - 37                      # ragged last tile
+    say(f"64->64 {dtype} tiles={n_tiles} n={n}")
+    side = int(np.ceil((n / 0.22) ** (1.0 / 3.0)))      # ~6 neighbours per voxel
+    coords = synth.uniform_cells(n, side, seed=n_tiles)
+    order = np.lexsort((coords[:, 3], coords[:, 2], coords[:, 1], coords[:, 0]))     # rows in x, y, z order
+    coords = np.ascontiguousarray(coords[order])
+    feat = synth.features(n, 64, dtype, 3)
+    weight = synth.weights(27, 64, 64, dtype, 3)
+    buf, h, out_coords, out = run_layer(coords, feat, weight, 3, 1, "subm", dtype, out_dtype="f32")
+    ref_km = oracle.kmap(coords, 3, 1, "subm")
+    assert h.n_pairs == ref_km["offset_start"][-1]
+    assert_maps_equal(exported_map(buf, h), out_coords, ref_km, exact_order=True)
+    rng = np.random.default_rng(n_tiles)
+    # a random sample, both ends, and whole tiles on either side of the places where one
+    # wavefront's share of the row range ends and the next one's begins
+    per_cu = -(-n_tiles // 256)
+    nwv = 4 if per_cu > 8 else per_cu
+    units = -(-n_tiles // nwv)
+    edges = [np.arange(max(0, w * units * 64 - 96), min(n, w * units * 64 + 96)) for w in range(1, nwv)]
+    rows = np.unique(np.concatenate([rng.choice(n, 4000, replace=False), np.arange(0, 130), np.arange(n - 130, n)] + edges))
+    ref = sampled_rows_reference(feat, weight, ref_km, rows)
+    err = rel_err(out[rows], ref[rows])
+    say(f"  sampled rows {len(rows)} max rel err {err:.3e}")
+    assert err <= 1e-5
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "target64"])
 def test_named_config_full(name):
     say(f"config {name}")
