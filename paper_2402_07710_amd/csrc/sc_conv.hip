@@ -479,7 +479,7 @@ __device__ inline f32x16 mfma32x32x16(u32x4 a, u32x4 b, f32x16 c) {
 }
 template <int N> struct IntC { static constexpr int value = N; };
 constexpr int DIRECT_STEPS(int K3) { return (K3 + 5) / 6 * 6; }      // six steps per trip of the loop
-constexpr int DIRECT_LINES(int K3) { return DIRECT_STEPS(K3) + 3; }  // table lines kept in LDS per wavefront
+constexpr int DIRECT_LINES(int K3) { return DIRECT_STEPS(K3) + 4; }  // table lines kept in LDS per wavefront
 constexpr int DIRECT_STAGE = 32 * 128;                               // bytes of a wavefront's staging area
 
 template <int DT, int K3, int FUSED>
@@ -573,11 +573,19 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
         st_r[i] = r32 * RB + (((2 * i + hh) ^ (r32 & 7)) << 4);
     }
     const int32_t* e_mine = e_lds + row8;
-    auto row_offsets = [&](uint32_t (&off)[2][4], int k) {
+    // row numbers of offset k for this lane's eight loads (read from LDS well ahead of their use), and
+    // the byte offsets made of them
+    auto row_numbers = [&](uint32_t (&e)[2][4], int k) {
 #pragma unroll
         for (int g = 0; g < 2; ++g)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) off[g][i] = ((uint32_t)e_mine[k * TILE + g * 32 + i * 8] << 7) | pbyte;
+            for (int i = 0; i < 4; ++i) e[g][i] = (uint32_t)e_mine[k * TILE + g * 32 + i * 8];
+    };
+    auto row_offsets = [&](uint32_t (&off)[2][4], const uint32_t (&e)[2][4]) {
+#pragma unroll
+        for (int g = 0; g < 2; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) off[g][i] = (e[g][i] << 7) | pbyte;
     };
     // the rows of one offset for the halves named by pat: four loads per half, skipped as a whole otherwise
     auto gather = [&](u32x4 (&dst)[2][4], const uint32_t (&off)[2][4], uint32_t pat) {
@@ -651,10 +659,13 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     load_weights(a[0], 0, pattern_at(0));
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
-        uint32_t off[2][4];
-        row_offsets(off, j);
+        uint32_t e[2][4], off[2][4];
+        row_numbers(e, j);
+        row_offsets(off, e);
         gather(fb[j], off, pattern_at(j));
     }
+    uint32_t e_next[2][4];               // row numbers of the offset the next step fetches
+    row_numbers(e_next, 3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
     for (int j = 0; j < 3; ++j) pin(fb[j]);
@@ -698,8 +709,6 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
         pin(fb[S1]);
         pin_w(a[AB]);
         load_weights(a[1 - AB], k + 1, pat1);
-        uint32_t off[2][4];
-        row_offsets(off, k + 3);       // read now, used after the multiplies have been issued
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl) {
 #pragma unroll
@@ -724,7 +733,10 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
                 }
             }
         }
+        uint32_t off[2][4];
+        row_offsets(off, e_next);
         gather(fb[S], off, pat3);
+        row_numbers(e_next, k + 4);     // on their way while the next step starts
     };
     // six steps per trip, so that ring slots (three) and weight registers (two sets) are constants
 #pragma unroll 1
