@@ -447,6 +447,8 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
 // with a handful of wavefronts, each of which walks its K^3 offsets as one chain; what a step of
 // that chain costs is the latency of what it has to wait for, so everything a step needs is
 // requested one to two steps ahead and a wavefront never waits for another one.
+//  * A wavefront walks only the offsets at which its tile has a neighbour at all (about 60 % of
+//    the 27 on surface-like sets), in increasing order, taken from the tile's masks bit by bit.
 //  * Multiplies are v_mfma_f32_32x32x16 on the two 32-row halves of the tile; a half without a
 //    neighbour at offset k is skipped, and so are its loads.
 //  * The weight operand of that instruction (32 output channels x 16 input channels) is read
@@ -478,21 +480,19 @@ __device__ inline f32x16 mfma32x32x16(u32x4 a, u32x4 b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 template <int N> struct IntC { static constexpr int value = N; };
-constexpr int DIRECT_STEPS(int K3) { return (K3 + 5) / 6 * 6; }      // six steps per trip of the loop
-constexpr int DIRECT_LINES(int K3) { return DIRECT_STEPS(K3) + 4; }  // table lines kept in LDS per wavefront
+constexpr int DIRECT_LINES(int K3) { return K3 + 1; }                // table lines kept in LDS per wavefront
 constexpr int DIRECT_STAGE = 32 * 128;                               // bytes of a wavefront's staging area
 
 template <int DT, int K3, int FUSED>
 __global__ void __launch_bounds__(512, 1)
 k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
                 const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
-    static_assert(K3 <= 60, "one 64-bit mask word per half, bits of the look-ahead included");
+    static_assert(K3 <= 31, "one mask word per half, and one more bit that is never set");
     static_assert(!FUSED || K3 == 27, "fused look-ups: 3x3x3 layers");
     const uint32_t* __restrict__ gmask = ms.gmask;
     const int32_t* __restrict__ nbr = ms.nbr;
     constexpr int MB = 2, C_out = 64, RB = 128;       // 32-channel output blocks, bytes per feature row
-    constexpr int KP = DIRECT_STEPS(K3);               // steps; the ones at or above K3 do nothing
-    constexpr int KE = DIRECT_LINES(K3);               // real lines, then lines of "no neighbour"
+    constexpr int KE = DIRECT_LINES(K3);               // the real lines, then one line of "no neighbour"
     extern __shared__ __align__(16) uint4 smem[];     // stage[NWV][32 rows x 128 B] | e_lds[NWV][KE][64]
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, NWV = blockDim.x >> 6;
@@ -511,7 +511,7 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     const int64_t tile = wv * units + unit;
     const bool tile_ok = tile * TILE < n_out;
 
-    uint64_t mg[2] = {0ull, 0ull};                     // which offsets each 32-row half takes part in (bits < K3)
+    uint32_t mg[2] = {0u, 0u};                         // which offsets each 32-row half takes part in (bits < K3)
     if constexpr (FUSED) {
         int32_t v[K3];
         if (tile_ok) {
@@ -520,7 +520,7 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
             for (int k = 0; k < K3; ++k) {
                 const uint64_t vote = __ballot(v[k] >= 0);
 #pragma unroll
-                for (int g = 0; g < 2; ++g) mg[g] |= (uint64_t)(((vote >> (32 * g)) & 0xffffffffull) != 0ull ? 1u : 0u) << k;
+                for (int g = 0; g < 2; ++g) mg[g] |= (((vote >> (32 * g)) & 0xffffffffull) != 0ull ? 1u : 0u) << k;
             }
         } else {
 #pragma unroll
@@ -548,9 +548,20 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
 #pragma unroll
     for (int k = K3; k < KE; ++k) e_lds[k * TILE + lane] = -1;
 #pragma unroll
-    for (int g = 0; g < 2; ++g) mg[g] = (uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)mg[g]);
-    auto pattern_at = [&](int k) -> uint32_t { return (uint32_t)((mg[0] >> k) & 1u) | ((uint32_t)((mg[1] >> k) & 1u) << 1); };
-    auto halves_at = [&](int k) -> uint32_t { return (uint32_t)((mg[0] >> k) & 1u) + (uint32_t)((mg[1] >> k) & 1u); };
+    for (int g = 0; g < 2; ++g) mg[g] = __builtin_amdgcn_readfirstlane(mg[g]);
+    auto pattern_at = [&](int k) -> uint32_t { return ((mg[0] >> k) & 1u) | (((mg[1] >> k) & 1u) << 1); };
+    auto halves_at = [&](int k) -> uint32_t { return ((mg[0] >> k) & 1u) + ((mg[1] >> k) & 1u); };
+    // The wavefront walks only the offsets its tile takes part in, in increasing order; K3 stands
+    // for "no further offset": no bit of the masks, a table line of "no neighbour".  k0 is the
+    // offset of the step at hand, k1..k4 the ones after it (what is requested ahead).
+    uint32_t rest = mg[0] | mg[1];
+    const int n_steps = __builtin_popcount(rest);
+    auto next_offset = [&]() -> int {
+        const int k = rest != 0u ? __builtin_ctz(rest) : K3;
+        rest &= rest - 1u;
+        return k;
+    };
+    int k0 = next_offset(), k1 = next_offset(), k2 = next_offset(), k3 = next_offset(), k4 = next_offset();
 
     // gathers: instruction i of a half reads its rows 8i .. 8i+7, eight lanes per row
     const int row8 = lane >> 3, piece = lane & 7;
@@ -655,17 +666,20 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
         for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) a[j][sl][mb] = u32x4{0u, 0u, 0u, 0u};
-    // before the loop: the weights of offset 0 and the rows of offsets 0..2, all complete at its start
-    load_weights(a[0], 0, pattern_at(0));
+    // before the loop: the weights of the first offset and the rows of the first three, all complete at its start
+    load_weights(a[0], k0, pattern_at(k0));
+    {
+        const int kj[3] = {k0, k1, k2};
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-        uint32_t e[2][4], off[2][4];
-        row_numbers(e, j);
-        row_offsets(off, e);
-        gather(fb[j], off, pattern_at(j));
+        for (int j = 0; j < 3; ++j) {
+            uint32_t e[2][4], off[2][4];
+            row_numbers(e, kj[j]);
+            row_offsets(off, e);
+            gather(fb[j], off, pattern_at(kj[j]));
+        }
     }
     uint32_t e_next[2][4];               // row numbers of the offset the next step fetches
-    row_numbers(e_next, 3);
+    row_numbers(e_next, k3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
     for (int j = 0; j < 3; ++j) pin(fb[j]);
@@ -677,10 +691,10 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[g][mb][j] = 0.f;
-    // rows of offset 0: load layout -> operand layout through the staging area (one half after the
-    // other through the same 4 KB: a wavefront's LDS operations execute in order)
+    // rows of the first offset: load layout -> operand layout through the staging area (one half after
+    // the other through the same 4 KB: a wavefront's LDS operations execute in order)
     {
-        const uint32_t pat0 = pattern_at(0);
+        const uint32_t pat0 = pattern_at(k0);
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             if ((pat0 >> g) & 1u) {
@@ -694,21 +708,25 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     SC_MARK(1);
     SC_MARK(2);
 
-    // One step.  At its start the rows of offset k are in ring slot S in operand layout and its
-    // weights are in a[AB] (possibly still on their way: the wait comes first); the rows of offset
-    // k+1 are in slot S1 in load layout, those of k+2 in flight.  Loads in issue order:
-    // ... weights k, rows k+2 | weights k+1, rows k+3: what may stay in flight at the top of step k
-    // are the rows of k+2, four loads per half that takes part.  Then the weights of offset k+1 are
-    // requested, the multiplies of offset k are issued slice by slice with the staging of offset
-    // k+1 between them (half 0 is written in slice 0 and read back in slice 1, half 1 in slices 2
-    // and 3), and the freed slot is refilled with the rows of offset k+3.
-    auto step = [&](auto slot_c, auto ab_c, int k) {
+    // One step, for offset k0.  At its start the rows of k0 are in ring slot S in operand layout and
+    // its weights are in a[AB] (possibly still on their way: the wait comes first); the rows of k1
+    // are in slot S1 in load layout, those of k2 in flight.  Loads in issue order:
+    // ... weights k0, rows k2 | weights k1, rows k3: what may stay in flight at the top of the step
+    // are the rows of k2, four loads per half that takes part.  Then the weights of k1 are
+    // requested, the multiplies of k0 are issued slice by slice with the staging of k1 between
+    // them (half 0 is written in slice 0 and read back in slice 1, half 1 in slices 2 and 3), the
+    // freed slot is refilled with the rows of k3, and the row numbers of k4 are read from LDS.
+    auto step = [&](auto slot_c, auto ab_c) {
         constexpr int S = decltype(slot_c)::value, S1 = (S + 1) % 3, AB = decltype(ab_c)::value;
-        const uint32_t pat = pattern_at(k), pat1 = pattern_at(k + 1), pat3 = pattern_at(k + 3);
-        wait_younger(halves_at(k + 2));
+        const uint32_t pat = pattern_at(k0), pat1 = pattern_at(k1), pat3 = pattern_at(k3);
+        wait_younger(halves_at(k2));
+        // every LDS operation of the step before is complete from here on (staging reads, row
+        // numbers): said in a form the compiler's wait-count pass sees, it places no LDS waits
+        // between the multiplies below, where they would also wait for the staging of this step
+        __builtin_amdgcn_s_waitcnt(0xc07f);      // lgkmcnt(0), the other counters left alone
         pin(fb[S1]);
         pin_w(a[AB]);
-        load_weights(a[1 - AB], k + 1, pat1);
+        load_weights(a[1 - AB], k1, pat1);
 #pragma unroll
         for (int sl = 0; sl < 4; ++sl) {
 #pragma unroll
@@ -736,17 +754,20 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
         uint32_t off[2][4];
         row_offsets(off, e_next);
         gather(fb[S], off, pat3);
-        row_numbers(e_next, k + 4);     // on their way while the next step starts
+        row_numbers(e_next, k4);        // on their way while the next step starts
+        k0 = k1; k1 = k2; k2 = k3; k3 = k4;
+        k4 = next_offset();
     };
-    // six steps per trip, so that ring slots (three) and weight registers (two sets) are constants
+    // six steps per trip, so that ring slots (three) and weight registers (two sets) are constants;
+    // steps past the last offset find K3 everywhere and do nothing
 #pragma unroll 1
-    for (int k = 0; k < KP; k += 6) {
-        step(IntC<0>{}, IntC<0>{}, k);
-        step(IntC<1>{}, IntC<1>{}, k + 1);
-        step(IntC<2>{}, IntC<0>{}, k + 2);
-        step(IntC<0>{}, IntC<1>{}, k + 3);
-        step(IntC<1>{}, IntC<0>{}, k + 4);
-        step(IntC<2>{}, IntC<1>{}, k + 5);
+    for (int i = 0; i < n_steps; i += 6) {
+        step(IntC<0>{}, IntC<0>{});
+        step(IntC<1>{}, IntC<1>{});
+        step(IntC<2>{}, IntC<0>{});
+        step(IntC<0>{}, IntC<1>{});
+        step(IntC<1>{}, IntC<0>{});
+        step(IntC<2>{}, IntC<1>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // nothing of the loop's loads is left in flight
     SC_MARK(3);
