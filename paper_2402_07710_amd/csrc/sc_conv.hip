@@ -449,8 +449,11 @@ k_conv_stream(const uint16_t* __restrict__ feat, const uint4* wp, void* __restri
 // requested one to two steps ahead and a wavefront never waits for another one.
 //  * A wavefront walks only the offsets at which its tile has a neighbour at all (about 60 % of
 //    the 27 on surface-like sets), in increasing order, taken from the tile's masks bit by bit.
-//  * Multiplies are v_mfma_f32_32x32x16 on the two 32-row halves of the tile; a half without a
-//    neighbour at offset k is skipped, and so are its loads.
+//  * Multiplies are v_mfma_f32_32x32x16 on the two 32-row halves of the tile.  SKIP = 1: a half
+//    without a neighbour at offset k is skipped, and so are its loads (tests and branches in
+//    every step, exact wait counts that depend on the tile).  SKIP = 0: such a half is rows of
+//    zeros like any row without a neighbour, and a step is one straight line of code, the same
+//    for every offset and tile; the host picks the form by how full the CUs are.
 //  * The weight operand of that instruction (32 output channels x 16 input channels) is read
 //    straight from the packed 16x32 tiles in global memory, one step ahead: both forms keep 8
 //    input channels of one output channel in 16 bytes, so only the addresses differ, and a load
@@ -483,7 +486,7 @@ template <int N> struct IntC { static constexpr int value = N; };
 constexpr int DIRECT_LINES(int K3) { return K3 + 1; }                // table lines kept in LDS per wavefront
 constexpr int DIRECT_STAGE = 32 * 128;                               // bytes of a wavefront's staging area
 
-template <int DT, int K3, int FUSED>
+template <int DT, int K3, int FUSED, int SKIP>
 __global__ void __launch_bounds__(512, 1)
 k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __restrict__ out, int out_f32,
                 const MapSource ms, const int64_t* __restrict__ n_out_ptr, int64_t n_out_cap) {
@@ -549,7 +552,7 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     for (int k = K3; k < KE; ++k) e_lds[k * TILE + lane] = -1;
 #pragma unroll
     for (int g = 0; g < 2; ++g) mg[g] = __builtin_amdgcn_readfirstlane(mg[g]);
-    auto pattern_at = [&](int k) -> uint32_t { return ((mg[0] >> k) & 1u) | (((mg[1] >> k) & 1u) << 1); };
+    auto pattern_at = [&](int k) -> uint32_t { return SKIP ? ((mg[0] >> k) & 1u) | (((mg[1] >> k) & 1u) << 1) : 3u; };
     auto halves_at = [&](int k) -> uint32_t { return ((mg[0] >> k) & 1u) + ((mg[1] >> k) & 1u); };
     // The wavefront walks only the offsets its tile takes part in, in increasing order; K3 stands
     // for "no further offset": no bit of the masks, a table line of "no neighbour".  k0 is the
@@ -602,6 +605,15 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     auto gather = [&](u32x4 (&dst)[2][4], const uint32_t (&off)[2][4], uint32_t pat) {
 #pragma unroll
         for (int g = 0; g < 2; ++g)
+            if constexpr (!SKIP)
+                asm volatile(
+                    "buffer_load_dwordx4 %[d0], %[o0], %[rs], 0 offen\n\t"
+                    "buffer_load_dwordx4 %[d1], %[o1], %[rs], 0 offen\n\t"
+                    "buffer_load_dwordx4 %[d2], %[o2], %[rs], 0 offen\n\t"
+                    "buffer_load_dwordx4 %[d3], %[o3], %[rs], 0 offen"
+                    : [d0] "+v"(dst[g][0]), [d1] "+v"(dst[g][1]), [d2] "+v"(dst[g][2]), [d3] "+v"(dst[g][3])
+                    : [o0] "v"(off[g][0]), [o1] "v"(off[g][1]), [o2] "v"(off[g][2]), [o3] "v"(off[g][3]), [rs] "s"(rs));
+            else
             asm volatile(
                 "s_bitcmp1_b32 %[pat], %[bit]\n\t"
                 "s_cbranch_scc0 .Lsc_skip_%=\n\t"
@@ -621,6 +633,20 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     auto load_weights = [&](u32x4 (&dst)[4][MB], int k, uint32_t pat) {
         const char* p0 = w_lane + (int64_t)(k < K3 ? k : K3 - 1) * (4 * MB * 1024);
         const char* p1 = p0 + 4096;
+        if constexpr (!SKIP)
+            asm volatile(
+                "global_load_dwordx4 %[d0], %[p0], off\n\t"
+                "global_load_dwordx4 %[d1], %[p1], off\n\t"
+                "global_load_dwordx4 %[d2], %[p0], off offset:512\n\t"
+                "global_load_dwordx4 %[d3], %[p1], off offset:512\n\t"
+                "global_load_dwordx4 %[d4], %[p0], off offset:1024\n\t"
+                "global_load_dwordx4 %[d5], %[p1], off offset:1024\n\t"
+                "global_load_dwordx4 %[d6], %[p0], off offset:1536\n\t"
+                "global_load_dwordx4 %[d7], %[p1], off offset:1536"
+                : [d0] "+v"(dst[0][0]), [d1] "+v"(dst[0][1]), [d2] "+v"(dst[1][0]), [d3] "+v"(dst[1][1]),
+                  [d4] "+v"(dst[2][0]), [d5] "+v"(dst[2][1]), [d6] "+v"(dst[3][0]), [d7] "+v"(dst[3][1])
+                : [p0] "v"(p0), [p1] "v"(p1));
+        else
         asm volatile(
             "s_cmp_eq_u32 %[pat], 0\n\t"
             "s_cbranch_scc1 .Lsc_skipw_%=\n\t"
@@ -640,9 +666,9 @@ k_conv_direct64(const uint16_t* __restrict__ feat, const uint4* wp, void* __rest
     };
     // wait until at most 4 n loads are outstanding (n: halves fetched by the step before)
     auto wait_younger = [&](uint32_t n) {
-        if (n == 0u) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (n == 1u) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        if (!SKIP || n == 2u) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (n == 0u) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     };
     // hand the registers of finished loads back to the compiler
     auto pin = [&](u32x4 (&slot)[2][4]) {
@@ -1043,7 +1069,7 @@ static int launch_stream(int64_t tiles, hipStream_t s, const uint16_t* feat, con
 // Up to 8 tiles per CU: one workgroup per CU with ceil(tiles / CUs) wavefronts (measured on ~110 k
 // voxels: 31.4 us with 7, 33.3 with 8, 35.1 with 4); beyond that, four (261 k voxels: 62.6 us
 // with 4, 64.0 with 8, 78.1 with 7).
-static int direct_tiles_per_workgroup(int64_t tiles) {
+static int direct_tiles_per_workgroup(int64_t tiles, int* cu_count_out) {
     static int cu_count[MAX_DEVICES] = {};      // per device, asked once (a race between host threads stores the same value)
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < MAX_DEVICES) {
@@ -1053,22 +1079,36 @@ static int direct_tiles_per_workgroup(int64_t tiles) {
         }
         cus = cu_count[dev];
     }
+    *cu_count_out = cus;
     if (tiles > (int64_t)cus * 8) return 4;
     const int64_t per_cu = (tiles + cus - 1) / cus;
     return per_cu < 1 ? 1 : (int)per_cu;
 }
+// SKIP = 1: halves of a tile without a neighbour at an offset are skipped together with their loads
+// (tests and branches in every step); SKIP = 0: a step is one straight line of code that treats
+// them as rows of zeros (about a sixth more loads, staging and multiplies on surface-like sets,
+// half the instructions).  The straight line wins while a CU has few wavefronts and the time is
+// one wavefront's walk over its offsets (14 k voxels: 15.2 against 19.2 us, 55 k: 20.8 against
+// 22.8), the skipping form once the CUs are full (110 k: 32.1 against 35.7, 261 k: 63.9 against 68.7).
+template <int DT, int K3, int FUSED, int SKIP>
+static int launch_direct64_as(int64_t tiles, int nwv, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out,
+                              int out_f32, const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
+    auto fn = k_conv_direct64<DT, K3, FUSED, SKIP>;
+    const size_t per_wave = DIRECT_STAGE + DIRECT_LINES(K3) * TILE * sizeof(int32_t);
+    static bool allowed[MAX_DEVICES] = {};
+    if (int rc = allow_lds((const void*)fn, 8 * per_wave, allowed)) return rc;
+    SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + nwv - 1) / nwv)), dim3(64 * nwv), nwv * per_wave, s, feat, wp, out,
+              out_f32, ms, counts, n_out_cap);
+    return SC_OK;
+}
 template <int DT, int K3, int FUSED>
 static int launch_direct64(int64_t tiles, hipStream_t s, const uint16_t* feat, const uint4* wp, void* out, int out_f32,
                            const MapSource& ms, const int64_t* counts, int64_t n_out_cap) {
-    auto fn = k_conv_direct64<DT, K3, FUSED>;
-    const size_t lds_max = (size_t)8 * (DIRECT_STAGE + DIRECT_LINES(K3) * TILE * sizeof(int32_t));
-    static bool allowed[MAX_DEVICES] = {};
-    if (int rc = allow_lds((const void*)fn, lds_max, allowed)) return rc;
-    const int nwv = direct_tiles_per_workgroup(tiles);
-    const size_t lds = (size_t)nwv * (DIRECT_STAGE + DIRECT_LINES(K3) * TILE * sizeof(int32_t));
-    SC_LAUNCH(KID_CONV_MFMA, fn, dim3(xcd_grid((tiles + nwv - 1) / nwv)), dim3(64 * nwv), lds, s, feat, wp, out, out_f32,
-              ms, counts, n_out_cap);
-    return SC_OK;
+    int cus = 256;
+    const int nwv = direct_tiles_per_workgroup(tiles, &cus);
+    if (tiles <= (int64_t)cus * 4)
+        return launch_direct64_as<DT, K3, FUSED, 0>(tiles, nwv, s, feat, wp, out, out_f32, ms, counts, n_out_cap);
+    return launch_direct64_as<DT, K3, FUSED, 1>(tiles, nwv, s, feat, wp, out, out_f32, ms, counts, n_out_cap);
 }
 
 // Up-sampling straight from the strided layer's map: shapes with a dedicated kernel.
