@@ -947,11 +947,13 @@ def test_cfg5_full_map_and_sampled_outputs():
     assert h.n_pairs == ref_km["offset_start"][-1]
     assert_maps_equal(exported_map(buf, h), out_coords, ref_km, exact_order=True)
     rng = np.random.default_rng(0)
-    # a random sample, both ends, and whole 64-row tiles on either side of every boundary between
-    # the eighths the convolution hands to the 8 XCDs (8 tiles per workgroup: the unit is 512 rows)
+    # a random sample, both ends, and whole 64-row tiles on either side of every place where the
+    # convolution's tile numbering changes hands: a workgroup of 8 wavefronts takes tiles
+    # w * units + unit (w = wavefront), and the units go to the 8 XCDs in eighths
     units = (n + 511) // 512
     chunk = (units + 7) // 8
-    edges = [np.arange(max(0, c * chunk * 512 - 128), min(n, c * chunk * 512 + 128)) for c in range(1, 8)]
+    edges = [np.arange(max(0, (w * units + c * chunk) * 64 - 128), min(n, (w * units + c * chunk) * 64 + 128))
+             for w in range(8) for c in range(8)]
     rows = np.unique(np.concatenate([rng.choice(n, 20000, replace=False), np.arange(0, 200), np.arange(n - 200, n)] + edges))
     keep = np.isin(ref_km["pair_out"], rows)
     ost = np.zeros(28, np.int64)
