@@ -429,6 +429,20 @@ def measure_layer(args, torch, sc, synth, workload: str, steps: int, warmup: int
         "roofline": roofline,
     }
 
+    # Multiplies issued against multiplies that exist.  The matrix kernels keep an output row in its
+    # place and skip a group of rows at an offset only if none of its rows has a neighbour there:
+    # 16 rows (v_mfma 16x16x32: k_conv_rows16, k_conv_stream) or 32 rows (32x32x16: k_conv_direct64).
+    # Counted from the exported pair lists, outside the timed region.
+    if conv_name == "k_conv_mfma" and args.table != "fused" and P > 0:
+        _, p_out, ost = sc.sc_kmap_export(buf.kmap, N, K, stride, mode, h, stream)
+        k_of = torch.bucketize(torch.arange(P, device=dev, dtype=torch.int32), ost[1:].contiguous(), right=True)
+        issued = {}
+        for rows, shift in ((16, 4), (32, 5)):
+            groups = torch.unique((p_out.long() >> shift) * (K ** 3) + k_of.long()).numel()
+            issued[f"groups_of_{rows}_rows"] = round(groups * rows / P, 3)
+        out["kernels"][conv_name]["multiplies_issued_over_active"] = issued
+        del p_out, ost, k_of
+
     # the same layer with the other location tables (same checks: the outputs must be identical),
     # for comparison: "grid" = dense array + kernel map, "fused" = dense array, look-ups inside the
     # convolution, no kernel map (3x3x3 16-bit layers with a dedicated kernel only)
