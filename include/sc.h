@@ -18,8 +18,8 @@
  *     borrowed for the duration of the stream work the call enqueues.  Pointers named h_* are
  *     host memory.  The library allocates nothing on the device (the measurement aids at the
  *     end of this file aside).  State it keeps between calls: per device, which kernels have
- *     been granted their large LDS allocation (set on first use) and the address of the array
- *     behind sc_kmap_build_noalloc; process-wide, the samples of the optional timing aid.
+ *     been granted their large LDS allocation (set on first use), its number of compute units
+ *     (asked once) and the address of the array behind sc_kmap_build_noalloc; process-wide, the samples of the optional timing aid.
  *     None of it changes results.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls except
  *     sc_counts_read (and sc_profile_read) are asynchronous on that stream and never synchronise.
