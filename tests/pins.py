@@ -332,6 +332,43 @@ def check_alg2_formulation(orc, rng, coords, K, stride, mode, C_in=3, C_out=2):
     np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-12)
 
 
+def group_sums_by_linearity(feat, weight, km, rows_per_group):
+    """Sums of the layer output over groups of consecutive output rows, without evaluating the
+    layer row by row: the sum over a group of sum_k in[i].W[k] is sum_k (sum of the input rows
+    the group gathers at k).W[k] - one sparse row-sum and one matrix product per offset.
+    Needs only a kernel map and library matrix products, so it reaches sizes at which the triple
+    loop takes minutes.  Returns [ceil(n_out / rows_per_group)][C_out] in float64."""
+    import scipy.sparse as sp
+    K3, C_in, C_out = weight.shape
+    n_in, n_out = feat.shape[0], int(km["n_out"])
+    n_groups = -(-n_out // rows_per_group)
+    f64, w64 = np.asarray(feat, dtype=np.float64), np.asarray(weight, dtype=np.float64)
+    ost = km["offset_start"]
+    total = np.zeros((n_groups, C_out))
+    for k in range(K3):
+        sl = slice(int(ost[k]), int(ost[k + 1]))
+        pi, po = np.asarray(km["pair_in"][sl], dtype=np.int64), np.asarray(km["pair_out"][sl], dtype=np.int64)
+        if pi.size == 0:
+            continue
+        gather = sp.csr_matrix((np.ones(pi.size), (po // rows_per_group, pi)), shape=(n_groups, n_in))
+        total += (gather @ f64) @ w64[k]
+    return total
+
+
+def check_group_sums(orc, rng, coords, K, stride, mode, rows_per_group, C_in=5, C_out=3):
+    """group_sums_by_linearity agrees with the oracle's output summed over the same groups."""
+    n = len(coords)
+    feat = rng.standard_normal((n, C_in))
+    W = rng.standard_normal((K ** 3, C_in, C_out))
+    _, out, km = orc.sparse_conv(coords, feat, W, K, stride, mode)
+    n_out = km["n_out"]
+    n_groups = -(-n_out // rows_per_group)
+    padded = np.zeros((n_groups * rows_per_group, C_out))
+    padded[:n_out] = out
+    ref = padded.reshape(n_groups, rows_per_group, C_out).sum(axis=1)
+    np.testing.assert_allclose(group_sums_by_linearity(feat, W, km, rows_per_group), ref, rtol=1e-11, atol=1e-11)
+
+
 def check_expected_pairs_uniform(orc):
     """Uniform-random occupancy (2,000 of 64³ cells): P = N + (ordered neighbour pairs), whose
     expectation is N(N-1)/(V-1) times the mean number of in-grid neighbours."""

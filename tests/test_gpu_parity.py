@@ -11,6 +11,7 @@ import torch
 import oracle
 from paper_2402_07710_amd import binding as sc
 from paper_2402_07710_amd import synth
+from tests import pins
 
 pytestmark = pytest.mark.gpu
 
@@ -965,3 +966,16 @@ def test_cfg5_full_map_and_sampled_outputs():
     err = rel_err(out[rows], ref[rows])
     say(f"  cfg5 sampled rows {len(rows)} max rel err {err:.3e}")
     assert err <= TOL["f16"]
+    # every row, through a property that holds at any size: the sum of each 64-row tile of the
+    # output equals sum_k (sum of the rows the tile gathers at k) . W[k] (tests/pins.py, checked
+    # against the oracle's row-by-row result in the CPU suite).  The outputs are fp16: a tile sum
+    # carries up to 64 roundings of 2^-11 relative each, ~2.5e-4 of the largest tile sum in
+    # practice, while one wrong or missing row moves its tile's sum by a few per cent of it.
+    tiles = -(-n // 64)
+    padded = np.zeros((tiles * 64, out.shape[1]))
+    padded[:n] = out
+    got = padded.reshape(tiles, 64, -1).sum(axis=1)
+    want = pins.group_sums_by_linearity(feat, weight, ref_km, 64)
+    err_t = rel_err(got, want)
+    say(f"  cfg5 sums of all {tiles} tiles: max rel err {err_t:.3e}")
+    assert err_t <= 2e-3

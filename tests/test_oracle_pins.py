@@ -77,6 +77,14 @@ def test_alg2_formulation(orc, K, s, mode):
     pins.check_alg2_formulation(orc, np.random.default_rng(6), c, K, s, mode)
 
 
+@pytest.mark.parametrize("K,s,mode,g", [(3, 1, "subm", 64), (3, 1, "subm", 7), (2, 2, "strided", 16), (3, 2, "strided", 5)])
+def test_group_sums_by_linearity(orc, K, s, mode, g):
+    """The whole-output check the full-size GPU test uses (sums over groups of output rows from a
+    map and matrix products alone) against the oracle's row-by-row result."""
+    c = synth.uniform_cells(300, 8, seed=11)
+    pins.check_group_sums(orc, np.random.default_rng(11), c, K, s, mode, g)
+
+
 @pytest.mark.parametrize("s", [2, 3])
 def test_inverse_is_adjoint(orc, s):
     c = synth.uniform_cells(400, 10, seed=8)
