@@ -476,6 +476,16 @@ def test_strided_general_on_lidar_scene():
     check_layer(coords, 3, 2, "strided", 32, 64, "f16", threads=16)
 
 
+@pytest.mark.parametrize("s", [2, 3])
+@pytest.mark.parametrize("dtype,n", [("f16", 700), ("bf16", 20000)])
+def test_strided_64_channel_layer(s, dtype, n):
+    """K = 3 strided layers of 64 -> 64 channels run the kernel of the 64-channel submanifold
+    layer: here its row count comes from the device and is far below the grid's row capacity."""
+    say(f"strided K=3 s={s} 64->64 {dtype} n={n}")
+    coords = synth.lidar_scene(6)[:n]
+    check_layer(coords, 3, s, "strided", 64, 64, dtype, seed=n, threads=16)
+
+
 @pytest.mark.parametrize("K", [1, 5, 7])
 def test_subm_other_kernel_sizes(K):
     say(f"subm K={K}")
@@ -660,7 +670,8 @@ def test_one_map_serves_several_layers():
     assert rel_err(out2.double().cpu().numpy(), oracle.conv(f2, w2, ref_km, threads=8)) <= TOL["f16"]
 
 
-@pytest.mark.parametrize("K,dtype,C_c,C_f", [(2, "f16", 64, 32), (2, "bf16", 128, 128), (3, "f16", 32, 32), (2, "f32", 8, 5)])
+@pytest.mark.parametrize("K,dtype,C_c,C_f", [(2, "f16", 64, 32), (2, "bf16", 128, 128), (3, "f16", 32, 32), (2, "f32", 8, 5),
+                                             (3, "f16", 64, 64), (3, "bf16", 64, 64)])
 def test_inverse_layer(K, dtype, C_c, C_f):
     """Up-sampling: the strided layer's map transposed; every fine row gets parent . W[offset]."""
     say(f"inverse K={K} {dtype}")
