@@ -840,6 +840,60 @@ def test_64_channel_layer_at_every_tiles_per_workgroup(n_tiles, dtype):
     assert err <= 1e-5
 
 
+@pytest.mark.parametrize("dims,C", [((257, 257, 257), 64), ((512, 256, 256), 32)])
+def test_layers_of_tens_of_millions_of_voxels(dims, C):
+    """Table, map and convolution far beyond the named workloads.  (257, 257, 257), 64 channels:
+    34 M voxels, the feature array passes 4 GiB, where the 64 -> 64 layer leaves the kernel with
+    32-bit buffer offsets for the streaming kernel.  (512, 256, 256), 32 channels: exactly
+    SC_N_MAX = 2^26 voxels, the largest input the library accepts.
+    The voxel set has a closed form: cells (3i+1, 3j+1, 3k+1) and (3i+1, 3j+1, 3k+2) for
+    (i, j, k) < dims, rows in that order, so row r has exactly one neighbour, row r^1, at dz = +1
+    (offset 14) for even r and dz = -1 (offset 12) for odd r, and out[r] = in[r].W[13] +
+    in[r^1].W[14 or 12] (the definition of the layer written out, Algorithm 2 with two terms),
+    evaluated here in float64 on sampled rows."""
+    I, J, Kd = dims
+    n = 2 * I * J * Kd
+    assert n <= sc.SC_N_MAX
+    say(f"{C}->{C} f16, n={n}: feature array {n * C * 2 / 2 ** 30:.2f} GiB")
+    r = torch.arange(n, device=DEV, dtype=torch.int64)
+    t, cell = r & 1, r >> 1
+    k, j, i = cell % Kd, (cell // Kd) % J, cell // (Kd * J)
+    d_coords = torch.stack([torch.zeros_like(r), 3 * i + 1, 3 * j + 1, 3 * k + 1 + t], dim=1).to(torch.int32).contiguous()
+    del r, t, cell, k, j, i
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(34)
+    d_feat = torch.randn((n, C), generator=gen, device=DEV, dtype=torch.float32).to(torch.float16)
+    weight = synth.weights(27, C, C, "f16", 34)
+    d_w = to_dev(weight, "f16")
+    buf = sc.LayerBuffers(n, 3, 1, "subm", C, C, "f16", device=DEV)
+    buf.layer(d_coords, d_feat, d_w)
+    h = buf.read_counts()
+    assert h.status == 0 and h.n_out == n and h.n_pairs == 2 * n
+    per_offset = [int(h.per_offset[q]) for q in range(27)]
+    assert per_offset[13] == n and per_offset[12] == n // 2 and per_offset[14] == n // 2 and sum(per_offset) == 2 * n
+    rng = np.random.default_rng(34)
+    mid = (1 << 32) // (2 * C)          # the row at byte 2^32 of the feature array
+    rows = np.unique(np.concatenate([rng.choice(n, 6000, replace=False), np.arange(0, 256), np.arange(n - 256, n),
+                                     np.arange(min(mid, n) - 256, min(mid + 256, n))]))
+    assert rows.min() >= 0 and rows.max() < n
+    idx = torch.from_numpy(rows).to(DEV)
+    f_own = d_feat[idx].double().cpu().numpy()
+    f_nb = d_feat[idx ^ 1].double().cpu().numpy()
+    w64 = weight.astype(np.float64)
+    k_nb = np.where(rows % 2 == 0, 14, 12)
+    ref = f_own @ w64[13] + np.einsum("rc,rcd->rd", f_nb, w64[k_nb])
+    got = buf.feat_out[idx].double().cpu().numpy()
+    err = rel_err(got, ref)
+    say(f"  sampled rows {len(rows)} max rel err {err:.3e}")
+    assert err <= TOL["f16"]
+    # the table itself on the sampled rows, through the library's look-up: the neighbour's row number
+    q = d_coords[idx].clone()
+    q[:, 3] += torch.from_numpy(np.where(rows % 2 == 0, 1, -1)).to(DEV).to(torch.int32)
+    found = torch.empty(len(rows), dtype=torch.int32, device=DEV)
+    sc.sc_hash_lookup(buf.table, n, q.contiguous(), found)
+    assert np.array_equal(found.cpu().numpy().astype(np.int64), rows ^ 1)
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "target64"])
 def test_named_config_full(name):
     say(f"config {name}")
