@@ -809,11 +809,9 @@ def sampled_rows_reference(feat, weight, ref_km, rows, threads=16):
 # The 64 -> 64 kernel puts 1..8 tiles into a workgroup depending on how many tiles there are per
 # CU (4 beyond 8 per CU), and spreads a workgroup's tiles over the row range: tile = wavefront *
 # units + unit.  One size per setting on a 256-CU device, fp32 output held to the fp32 tolerance.
-@pytest.mark.parametrize("n_tiles", [255, 300, 600, 1000, 1200, 1500, 1700, 2040, 2300])
-@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("n_tiles,dtype", [(t, "f16") for t in (255, 300, 600, 1000, 1200, 1500, 1700, 2040, 2300)] +
+                         [(t, "bf16") for t in (300, 1700, 2300)])
 def test_64_channel_layer_at_every_tiles_per_workgroup(n_tiles, dtype):
-    if dtype == "bf16" and n_tiles not in (300, 1700, 2300):
-        pytest.skip("bf16: three sizes")
     n = n_tiles * 64 - 37                      # ragged last tile
     say(f"64->64 {dtype} tiles={n_tiles} n={n}")
     side = int(np.ceil((n / 0.22) ** (1.0 / 3.0)))      # ~6 neighbours per voxel
