@@ -27,6 +27,12 @@ MUTANTS = {
     "overwrite_instead_of_accumulate": ("fo[co] += fi[ci]", "fo[co] = fi[ci]"),
     "y_offset_uses_x": ("outs[o][2] * stride + d[1] - pad", "outs[o][2] * stride + d[0] - pad"),
     "input_channel_off_by_one": ("for (int ci = 0; ci < C_in; ++ci)", "for (int ci = 1; ci < C_in; ++ci)"),
+    "z_offset_uses_y": ("outs[o][3] * stride + d[2] - pad", "outs[o][3] * stride + d[1] - pad"),
+    "output_cell_offset_sign": ("int32_t t = coords[4 * i + 1 + a] - d[a];", "int32_t t = coords[4 * i + 1 + a] + d[a];"),
+    "offsets_reversed_in_the_sum": ("const double* Wk = weight + (size_t)k * C_in * C_out;",
+                                    "const double* Wk = weight + (size_t)(K3 - 1 - k) * C_in * C_out;"),
+    "strided_layers_padded": ("(mode == 0) ? (K - 1) / 2 : 0", "(K - 1) / 2"),
+    "output_row_of_a_pair_shifted": ("pair_out[total] = (int32_t)o;", "pair_out[total] = (int32_t)((o + 1) % outs.size());"),
 }
 
 
