@@ -34,7 +34,7 @@ PEAK_FP32_TFLOPS = 157.3       # fp32 vector ALU
 
 def algorithmic_bytes(kernel: str, st: dict) -> float | None:
     """Bytes one launch of `kernel` has to move by the method's own accounting: a per-unit figure
-    times the units one launch processes (both are stated in the design doc)."""
+    (the comment on each case below) times the units one launch processes."""
     N, N_out, P, K3, cap = st["N"], st["N_out"], st["P"], st["K3"], st["cap"]
     C_in, C_out, e = st["C_in"], st["C_out"], st["elem_bytes"]
     if kernel == "k_table_fill":
